@@ -1,0 +1,212 @@
+/* arb.h - C ABI of libarb: the batched step-scoring forward and routing decision
+ * of Arbitrage (step-level speculative generation), for one AMD MI355X (gfx950).
+ *
+ * The method (paper Section 4.2, Fig. 1, Algorithm 1): at every reasoning step
+ * a draft model proposes a step z_d for the context x; a router
+ * h_router(x, z_d) gives a score y_hat; the draft is ACCEPTED iff y_hat <= tau
+ * and the step is ESCALATED to the target model iff y_hat > tau; the target then
+ * regenerates the step "from the same prefix" x.  The router is a decoder-only
+ * transformer with a classification head.  This library runs that transformer
+ * over the drafted steps of a batch of independent sequences, against their
+ * cached (block-paged) prefixes, and takes the decision.  The same forward
+ * without the head is the target model's pass over an appended step.
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory on the current device; "host"
+ *    pointers are ordinary host memory.  The caller owns every buffer, including
+ *    the KV pool and the workspace; the library allocates nothing in the hot
+ *    calls (arb_prefill, arb_score_steps, arb_route and the arb_stage_* calls),
+ *    never synchronises the device and never reads results back.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream).  Outputs are valid once the caller has synchronised it.
+ *  - Every call returns an arb_status; nothing throws or aborts across the ABI.
+ *    arb_last_error() gives a message for the last failing call of this thread.
+ *  - bf16 = the upper 16 bits of an IEEE fp32, round-to-nearest-even.
+ *  - Lengths are stateless: each call is told prefix_lens and the step lengths;
+ *    the step's keys/values are written at positions [p_b, p_b+s_b) of sequence
+ *    b and nothing records that.  Rejecting a draft (Alg. 1, escalate branch) is
+ *    not advancing prefix_lens; accepting it (x <- x || z) is advancing it by s_b.
+ *    Repeating a call with the same arguments gives the same results.
+ *
+ * Supported shapes: head_dim == 64 or 128; d_model, d_ffn and n_q_heads*head_dim multiples of
+ * 128; n_q_heads a multiple of n_kv_heads; kv_block == 16.  Others -> ARB_EUNSUPPORTED.
+ */
+#ifndef ARB_H
+#define ARB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ARB_OK = 0,
+  ARB_EINVAL = 1,       /* null pointer, negative size, empty step (s_b == 0), inconsistent cu_step_lens */
+  ARB_ESHAPE = 2,       /* n_q_heads % n_kv_heads != 0, odd head_dim, non-positive dimension */
+  ARB_ECAPACITY = 3,    /* block table row or workspace too small for the call */
+  ARB_EHIP = 4,         /* a HIP runtime call failed (message has the HIP error string) */
+  ARB_EUNSUPPORTED = 5  /* a valid shape this build has no kernel for */
+} arb_status;
+
+/* How the step's hidden states are pooled before the head.  MEAN over the s_b
+ * step tokens is what the workload configs use; LAST is the paper's statement
+ * that the classification head sits on the final-token embedding (Section 4.2,
+ * "Training"). */
+typedef enum { ARB_POOL_MEAN = 0, ARB_POOL_LAST = 1 } arb_pool_mode;
+
+/* Comparison sense.  ARB_ESCALATE_IF_GT is Arbitrage: accept iff score <= tau
+ * (Fig. 1, Alg. 1).  ARB_ACCEPT_IF_GT is the RSD baseline: accept iff
+ * score > tau (Section 3.1).  In both, a NaN score escalates. */
+typedef enum { ARB_ESCALATE_IF_GT = 0, ARB_ACCEPT_IF_GT = 1 } arb_route_sense;
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps;        /* added to the mean square under the root */
+  float rope_base;      /* rotary angle of pair t at position pos: pos * base^(-2t/head_dim) */
+  int32_t kv_block;     /* tokens per KV block (16) */
+  int32_t pool;         /* arb_pool_mode */
+  int32_t has_router_head; /* 0: target pass (hidden states only) */
+} arb_model_cfg;
+
+/* Weights.  All DEVICE pointers, caller-owned, must outlive the model.  The
+ * per-layer arrays themselves (wqkv[l], ...) are HOST arrays of n_layers device
+ * pointers and are copied by arb_model_create.
+ * Every matrix is bf16, row-major [out_features, in_features] (y = x W^T):
+ *   embed [vocab, d]
+ *   wqkv  [(Hq + 2 Hkv) * hd, d]  rows: Hq query heads, then Hkv key heads, then Hkv value heads
+ *   wo    [d, Hq * hd]
+ *   wgu   [2 F, d]                rows: F gate rows, then F up rows; MLP = (silu(x Wg^T) * (x Wu^T)) Wd^T
+ *   wd    [d, F]
+ * RMSNorm gains g_attn[l], g_mlp[l], g_final are fp32 [d]; w_head is fp32 [d]
+ * (NULL when has_router_head == 0); b_head is the head's scalar bias. */
+typedef struct {
+  const void *embed;
+  const void *const *wqkv, *const *wo, *const *wgu, *const *wd;
+  const float *const *g_attn, *const *g_mlp;
+  const float *g_final;
+  const float *w_head;
+  float b_head;
+} arb_weights;
+
+/* Paged KV cache.  k_pool / v_pool are HOST arrays of n_layers DEVICE pointers;
+ * each pool is bf16 [n_blocks, Hkv, kv_block, head_dim].  Position pos of
+ * sequence b lives in block block_tables[b][pos / kv_block] at row pos % kv_block.
+ * Keys are stored after the rotary embedding.  The calls write only the slots of
+ * the step's own positions. */
+typedef struct {
+  void *const *k_pool, *const *v_pool;
+  int32_t n_blocks;
+} arb_kv;
+
+/* One batch of B independent sequences: a cached prefix of prefix_lens[b] tokens
+ * and a new step of s_b = cu_step_lens[b+1] - cu_step_lens[b] >= 1 tokens whose
+ * ids are token_ids[cu_step_lens[b] .. cu_step_lens[b+1]).  The two length arrays
+ * are given twice: on the device for the kernels, on the host for validation and
+ * launch sizing.  Block-table contents are trusted (not range-checked). */
+typedef struct {
+  int32_t batch, total_tokens, max_blocks_per_seq;
+  const int32_t *token_ids;          /* device [total_tokens] */
+  const int32_t *block_tables;       /* device [batch, max_blocks_per_seq] */
+  const int32_t *prefix_lens;        /* device [batch] */
+  const int32_t *cu_step_lens;       /* device [batch + 1] */
+  const int32_t *prefix_lens_host;   /* host   [batch] */
+  const int32_t *cu_step_lens_host;  /* host   [batch + 1] */
+} arb_batch;
+
+typedef struct arb_model arb_model;
+
+/* Validates the shape and copies the configuration and pointer tables (host
+ * memory only).  *out is owned by the caller until arb_model_destroy. */
+arb_status arb_model_create(const arb_model_cfg *cfg, const arb_weights *w, arb_model **out);
+arb_status arb_model_destroy(arb_model *m);
+
+/* Bytes of device workspace the hot calls need for batches of at most
+ * max_total_tokens step tokens in at most max_batch sequences whose context
+ * (prefix + step) is at most max_ctx tokens.  0 on invalid arguments. */
+size_t arb_workspace_bytes(const arb_model *m, int32_t max_batch, int32_t max_total_tokens, int32_t max_ctx);
+
+/* The router forward (Section 4.2; Alg. 1 "routing decision") or, with
+ * has_router_head == 0, the target's pass over an appended step.
+ *   scores     device fp32 [batch]: y_hat_b = w_head . pool_b(final-normed hidden) + b_head;
+ *              required iff has_router_head, else must be NULL
+ *   escalate   device uint8 [batch] or NULL: 1 iff not (y_hat_b <= tau)
+ *   hidden_out device bf16 [total_tokens, d_model] or NULL: final-normed hidden states
+ *   ws         device workspace of ws_bytes >= arb_workspace_bytes(...)
+ * Side effect: the step's rotary keys and values are stored (bf16) at its slots
+ * in every layer's pool.  batch == 0 is a no-op. */
+arb_status arb_score_steps(arb_model *m, const arb_kv *kv, const arb_batch *batch, float tau, float *scores,
+                           uint8_t *escalate, void *hidden_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Fills the cache for whole prompts: the same forward with the "step" being the
+ * prompt (prefix_lens normally all 0; a non-zero prefix continues a chunked
+ * prefill).  No head.  hidden_out as above, may be NULL. */
+arb_status arb_prefill(arb_model *m, const arb_kv *kv, const arb_batch *batch, void *hidden_out, void *ws,
+                       size_t ws_bytes, void *stream);
+
+/* The decision alone (Fig. 1; Alg. 1; Section 3.1 for the RSD sense), so that
+ * tau can be swept without repeating the forward.  Also serves the oracle
+ * policy a*_tau = 1{Delta > tau} (Eq. 4.4) when `scores` holds advantages.
+ * scores: device fp32 [n]; escalate: device uint8 [n].  n == 0 is a no-op. */
+arb_status arb_route(const float *scores, int32_t n, float tau, int32_t sense, uint8_t *escalate, void *stream);
+
+/* Pool slot of every step token, slot = block_tables[b][pos/kv_block]*kv_block + pos%kv_block with
+ * pos = prefix_lens[b] + i, as the forward computes it.  slots: device int32 [total_tokens]. */
+arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream);
+
+/* ---- single stages of the forward, exposed so each kernel can be checked and
+ * timed on its own at full size.  Same pointer conventions as above. ---- */
+
+typedef enum {
+  ARB_EPI_STORE_BF16 = 0,   /* C bf16 [M, N] = A B^T */
+  ARB_EPI_RESIDUAL_F32 = 1, /* C fp32 [M, N] += A B^T */
+  ARB_EPI_SWIGLU_BF16 = 2   /* B is [2F, K] (gate rows, up rows); C bf16 [M, F] = silu(A Bg^T) * (A Bu^T); N = F */
+} arb_gemm_epilogue;
+
+/* Projection GEMM: A bf16 [M, K] row-major, B bf16 [N, K] row-major (weights),
+ * fp32 accumulation.  K % 64 == 0 and N % 128 == 0 (N % 64 == 0 for SWIGLU). */
+arb_status arb_stage_gemm(const void *A, const void *B, void *C, int32_t M, int32_t N, int32_t K, int32_t epilogue,
+                          void *stream);
+
+/* Append-attention of one layer.  q: device bf16, row t at q + t*q_row_stride elements, heads contiguous
+ * [Hq, hd], already rotated; the pools already hold the step's keys/values.  out: bf16 [T, Hq*hd]. */
+arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, const void *k_pool,
+                               const void *v_pool, const arb_batch *batch, void *out, void *ws, size_t ws_bytes,
+                               void *stream);
+
+/* RMSNorm rows: x fp32 [T, d] -> out bf16 [T, d] = x / sqrt(mean(x^2) + eps) * g. */
+arb_status arb_stage_rmsnorm(const float *x, const float *g, float eps, int32_t T, int32_t d, void *out, void *stream);
+
+/* Rotary embedding of the q and k heads of qkv (bf16 [T, (Hq+2Hkv)*hd], q rotated in place) at
+ * positions prefix_lens[b] + i, and the K/V append into one layer's pool. */
+arb_status arb_stage_rope_append(const arb_model *m, void *qkv, void *k_pool, void *v_pool, const arb_batch *batch,
+                                 void *ws, size_t ws_bytes, void *stream);
+
+/* Final RMSNorm of the residual stream h (fp32 [T, d]) followed by pooling, head and threshold
+ * (Section 4.2; Alg. 1): hidden_out bf16 [T, d] or NULL; scores fp32 [batch]; escalate uint8 [batch] or
+ * NULL.  The head is applied to the unrounded fp32 normed states.  ws: >= 4*T bytes. */
+arb_status arb_stage_norm_pool_head(const float *h, const float *g_final, float eps, const arb_batch *batch,
+                                    int32_t d, const float *w_head, float b_head, int32_t pool, float tau,
+                                    void *hidden_out, float *scores, uint8_t *escalate, void *ws, size_t ws_bytes,
+                                    void *stream);
+
+/* Timing hook for measurement harnesses (no paper passage: it computes nothing).
+ * While armed, arb_score_steps / arb_prefill record start[i] before and stop[i]
+ * after their i-th launch of the given stage on the call's stream, for i < n.
+ * start/stop are HOST arrays of n hipEvent_t created by the caller with timing
+ * enabled; they must stay valid while armed.  arb_model_trace_count gives the
+ * number of launches recorded since arming.  n == 0 disarms. */
+typedef enum {
+  ARB_STAGE_QKV = 0, ARB_STAGE_ATTENTION = 1, ARB_STAGE_OPROJ = 2, ARB_STAGE_GATE_UP = 3, ARB_STAGE_DOWN = 4,
+  ARB_STAGE_NORM = 5, ARB_STAGE_ROPE_APPEND = 6
+} arb_trace_stage;
+arb_status arb_model_trace(arb_model *m, int32_t stage, void *const *start, void *const *stop, int32_t n);
+int32_t arb_model_trace_count(const arb_model *m);
+
+const char *arb_last_error(void); /* thread-local; valid until the next call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARB_H */

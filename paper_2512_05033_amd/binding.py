@@ -1,0 +1,348 @@
+"""ctypes binding of libarb (include/arb.h): argument marshalling only.
+
+Every step of the forward runs in the library's HIP kernels; torch is used for
+device memory and for the current stream.  There is no fallback path: if the
+shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libarb.so")
+_lib = None
+
+ARB_OK, ARB_EINVAL, ARB_ESHAPE, ARB_ECAPACITY, ARB_EHIP, ARB_EUNSUPPORTED = range(6)
+ARB_POOL_MEAN, ARB_POOL_LAST = 0, 1
+ARB_ESCALATE_IF_GT, ARB_ACCEPT_IF_GT = 0, 1
+ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16 = 0, 1, 2
+(ARB_STAGE_QKV, ARB_STAGE_ATTENTION, ARB_STAGE_OPROJ, ARB_STAGE_GATE_UP, ARB_STAGE_DOWN, ARB_STAGE_NORM,
+ ARB_STAGE_ROPE_APPEND) = range(7)
+_STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4: "ARB_EHIP", 5: "ARB_EUNSUPPORTED"}
+
+EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
+           "arb_route", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
+           "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_model_trace", "arb_model_trace_count",
+           "arb_last_error"]
+
+
+class ArbError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("kv_block", C.c_int32), ("pool", C.c_int32),
+                ("has_router_head", C.c_int32)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("wqkv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)),
+                ("wgu", C.POINTER(C.c_void_p)), ("wd", C.POINTER(C.c_void_p)), ("g_attn", C.POINTER(C.c_void_p)),
+                ("g_mlp", C.POINTER(C.c_void_p)), ("g_final", C.c_void_p), ("w_head", C.c_void_p),
+                ("b_head", C.c_float)]
+
+
+class _KV(C.Structure):
+    _fields_ = [("k_pool", C.POINTER(C.c_void_p)), ("v_pool", C.POINTER(C.c_void_p)), ("n_blocks", C.c_int32)]
+
+
+class _Batch(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("total_tokens", C.c_int32), ("max_blocks_per_seq", C.c_int32),
+                ("token_ids", C.c_void_p), ("block_tables", C.c_void_p), ("prefix_lens", C.c_void_p),
+                ("cu_step_lens", C.c_void_p), ("prefix_lens_host", C.c_void_p), ("cu_step_lens_host", C.c_void_p)]
+
+
+def load_library(path: Optional[str] = None):
+    """Loads libarb.so (built in-tree by build.py).  Raises if it is not there."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or _LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built; run `python -m paper_2512_05033_amd.build` "
+                           "(there is no fallback implementation)")
+    lib = C.CDLL(path)
+    lib.arb_last_error.restype = C.c_char_p
+    lib.arb_workspace_bytes.restype = C.c_size_t
+    lib.arb_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
+    lib.arb_model_create.argtypes = [C.POINTER(_Cfg), C.POINTER(_Weights), C.POINTER(C.c_void_p)]
+    lib.arb_model_destroy.argtypes = [C.c_void_p]
+    lib.arb_score_steps.argtypes = [C.c_void_p, C.POINTER(_KV), C.POINTER(_Batch), C.c_float, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_prefill.argtypes = [C.c_void_p, C.POINTER(_KV), C.POINTER(_Batch), C.c_void_p, C.c_void_p, C.c_size_t,
+                                C.c_void_p]
+    lib.arb_route.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.arb_slot_mapping.argtypes = [C.POINTER(_Batch), C.c_int32, C.c_void_p, C.c_void_p]
+    lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                   C.c_void_p]
+    lib.arb_stage_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(_Batch),
+                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_stage_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.arb_stage_rope_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_Batch),
+                                          C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_stage_norm_pool_head.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.POINTER(_Batch), C.c_int32,
+                                             C.c_void_p, C.c_float, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_model_trace.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32]
+    lib.arb_model_trace_count.argtypes = [C.c_void_p]
+    lib.arb_model_trace_count.restype = C.c_int32
+    for name in EXPORTS:
+        if name not in ("arb_last_error", "arb_workspace_bytes", "arb_model_trace_count"):
+            getattr(lib, name).restype = C.c_int
+    if path == _LIB_PATH:
+        _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != ARB_OK:
+        raise ArbError(status, load_library().arb_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _ptr_array(tensors: Sequence[torch.Tensor]):
+    return (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"expected a contiguous cuda tensor of {dtype}, got {t.dtype} on {t.device}")
+    return t
+
+
+class Model:
+    """An arb_model plus the tensors it points at (kept alive here)."""
+
+    def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, weights,
+                 rms_eps=1e-6, rope_base=10000.0, kv_block=16, pool=ARB_POOL_MEAN, has_router_head=True):
+        lib = load_library()
+        w = weights
+        bf, f32 = torch.bfloat16, torch.float32
+        self._keep = [_dev(w.embed, bf), *[_dev(t, bf) for l in (w.wqkv, w.wo, w.wgu, w.wd) for t in l],
+                      *[_dev(t, f32) for l in (w.g_attn, w.g_mlp) for t in l], _dev(w.g_final, f32)]
+        if has_router_head:
+            self._keep.append(_dev(w.w_head, f32))
+        self.cfg = _Cfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rms_eps, rope_base,
+                        kv_block, pool, int(has_router_head))
+        self._arrays = [_ptr_array(l) for l in (w.wqkv, w.wo, w.wgu, w.wd, w.g_attn, w.g_mlp)]
+        cw = _Weights(w.embed.data_ptr(), *self._arrays, w.g_final.data_ptr(),
+                      w.w_head.data_ptr() if has_router_head else None, float(w.b_head))
+        self.handle = C.c_void_p()
+        _check(lib.arb_model_create(C.byref(self.cfg), C.byref(cw), C.byref(self.handle)))
+        self.weights = w
+        self.device = w.embed.device
+
+    def workspace_bytes(self, max_batch: int, max_total_tokens: int, max_ctx: int) -> int:
+        return int(load_library().arb_workspace_bytes(self.handle, max_batch, max_total_tokens, max_ctx))
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().arb_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class KVCache:
+    """Per-layer K and V pools, bf16 [n_blocks, Hkv, kv_block, head_dim] on the device."""
+
+    def __init__(self, k_pools: List[torch.Tensor], v_pools: List[torch.Tensor]):
+        self.k_pools = [_dev(t, torch.bfloat16) for t in k_pools]
+        self.v_pools = [_dev(t, torch.bfloat16) for t in v_pools]
+        self._k, self._v = _ptr_array(self.k_pools), _ptr_array(self.v_pools)
+        self.c = _KV(self._k, self._v, int(k_pools[0].shape[0]))
+
+
+class DeviceBatch:
+    """Lengths on host and device, block tables and token ids on the device."""
+
+    def __init__(self, prefix_lens, cu_step_lens, block_tables, token_ids=None, device="cuda"):
+        self.prefix_host = np.ascontiguousarray(prefix_lens, dtype=np.int32)
+        self.cu_host = np.ascontiguousarray(cu_step_lens, dtype=np.int32)
+        tables = np.ascontiguousarray(block_tables, dtype=np.int32)
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+        self.prefix, self.cu, self.tables = to(self.prefix_host), to(self.cu_host), to(tables)
+        self.tokens = None if token_ids is None else to(token_ids)
+        self.batch = len(self.prefix_host)
+        self.total_tokens = int(self.cu_host[-1]) if len(self.cu_host) else 0
+        self.c = _Batch(self.batch, self.total_tokens, tables.shape[1] if tables.ndim == 2 else 0,
+                        _ptr(self.tokens), _ptr(self.tables), _ptr(self.prefix), _ptr(self.cu),
+                        self.prefix_host.ctypes.data, self.cu_host.ctypes.data)
+
+    @property
+    def max_ctx(self) -> int:
+        return int((self.prefix_host + np.diff(self.cu_host)).max()) if self.batch else 0
+
+
+def _workspace(model: Model, batch: DeviceBatch, ws: Optional[torch.Tensor]) -> torch.Tensor:
+    if ws is None:
+        n = model.workspace_bytes(batch.batch, batch.total_tokens, batch.max_ctx)
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device=model.device)
+    return ws
+
+
+def arb_score_steps(model: Model, kv: KVCache, batch: DeviceBatch, tau: float, *, want_hidden: bool = False,
+                    ws: Optional[torch.Tensor] = None, scores=None, escalate=None, hidden=None, stream=None):
+    """-> (scores fp32 [B] or None, escalate uint8 [B] or None, hidden bf16 [T, d] or None)."""
+    head = bool(model.cfg.has_router_head)
+    dev = model.device
+    if head and scores is None:
+        scores = torch.empty(batch.batch, dtype=torch.float32, device=dev)
+    if head and escalate is None:
+        escalate = torch.empty(batch.batch, dtype=torch.uint8, device=dev)
+    if want_hidden and hidden is None:
+        hidden = torch.empty(batch.total_tokens, model.cfg.d_model, dtype=torch.bfloat16, device=dev)
+    ws = _workspace(model, batch, ws)
+    _check(load_library().arb_score_steps(model.handle, C.byref(kv.c), C.byref(batch.c), float(tau), _ptr(scores),
+                                          _ptr(escalate), _ptr(hidden), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return scores, escalate, hidden
+
+
+def arb_prefill(model: Model, kv: KVCache, batch: DeviceBatch, *, want_hidden: bool = False,
+                ws: Optional[torch.Tensor] = None, stream=None):
+    hidden = None
+    if want_hidden:
+        hidden = torch.empty(batch.total_tokens, model.cfg.d_model, dtype=torch.bfloat16, device=model.device)
+    ws = _workspace(model, batch, ws)
+    _check(load_library().arb_prefill(model.handle, C.byref(kv.c), C.byref(batch.c), _ptr(hidden), ws.data_ptr(),
+                                      ws.numel(), _stream(stream)))
+    return hidden
+
+
+def arb_route(scores: torch.Tensor, tau: float, sense: int = ARB_ESCALATE_IF_GT, stream=None) -> torch.Tensor:
+    _dev(scores, torch.float32)
+    out = torch.empty(scores.numel(), dtype=torch.uint8, device=scores.device)
+    _check(load_library().arb_route(_ptr(scores), scores.numel(), float(tau), sense, _ptr(out), _stream(stream)))
+    return out
+
+
+def arb_slot_mapping(batch: DeviceBatch, kv_block: int = 16, stream=None) -> torch.Tensor:
+    out = torch.empty(batch.total_tokens, dtype=torch.int32, device=batch.tables.device)
+    _check(load_library().arb_slot_mapping(C.byref(batch.c), kv_block, _ptr(out), _stream(stream)))
+    return out
+
+
+def arb_stage_gemm(a: torch.Tensor, b: torch.Tensor, epilogue: int = ARB_EPI_STORE_BF16,
+                   out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """a bf16 [M, K], b bf16 [N, K] (or [2F, K] for SwiGLU) -> [M, N] (or [M, F])."""
+    _dev(a, torch.bfloat16), _dev(b, torch.bfloat16)
+    M, K = a.shape
+    N = b.shape[0] // 2 if epilogue == ARB_EPI_SWIGLU_BF16 else b.shape[0]
+    if b.shape[1] != K:
+        raise ValueError("inner dimensions differ")
+    if out is None:
+        if epilogue == ARB_EPI_RESIDUAL_F32:
+            raise ValueError("the residual epilogue accumulates into `out`")
+        out = torch.empty(M, N, dtype=torch.bfloat16, device=a.device)
+    _dev(out, torch.float32 if epilogue == ARB_EPI_RESIDUAL_F32 else torch.bfloat16)
+    if tuple(out.shape) != (M, N):
+        raise ValueError("output shape")
+    _check(load_library().arb_stage_gemm(_ptr(a), _ptr(b), _ptr(out), M, N, K, epilogue, _stream(stream)))
+    return out
+
+
+def arb_stage_attention(model: Model, q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
+                        batch: DeviceBatch, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q bf16 [T, row] whose first Hq*hd columns are the (rotated) query heads -> bf16 [T, Hq*hd]."""
+    _dev(q, torch.bfloat16), _dev(k_pool, torch.bfloat16), _dev(v_pool, torch.bfloat16)
+    out = torch.empty(batch.total_tokens, model.cfg.n_q_heads * model.cfg.head_dim, dtype=torch.bfloat16,
+                      device=q.device)
+    ws = _workspace(model, batch, ws)
+    _check(load_library().arb_stage_attention(model.handle, _ptr(q), q.shape[1], _ptr(k_pool), _ptr(v_pool),
+                                              C.byref(batch.c), _ptr(out), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return out
+
+
+def arb_stage_rmsnorm(x: torch.Tensor, g: torch.Tensor, eps: float, stream=None) -> torch.Tensor:
+    _dev(x, torch.float32), _dev(g, torch.float32)
+    out = torch.empty(x.shape, dtype=torch.bfloat16, device=x.device)
+    _check(load_library().arb_stage_rmsnorm(_ptr(x), _ptr(g), float(eps), x.shape[0], x.shape[1], _ptr(out),
+                                            _stream(stream)))
+    return out
+
+
+def arb_stage_rope_append(model: Model, qkv: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
+                          batch: DeviceBatch, stream=None) -> None:
+    """Rotates the q heads of qkv in place and appends rotated k and v to the pool."""
+    _dev(qkv, torch.bfloat16), _dev(k_pool, torch.bfloat16), _dev(v_pool, torch.bfloat16)
+    ws = _workspace(model, batch, None)
+    _check(load_library().arb_stage_rope_append(model.handle, _ptr(qkv), _ptr(k_pool), _ptr(v_pool), C.byref(batch.c),
+                                                ws.data_ptr(), ws.numel(), _stream(stream)))
+
+
+def arb_stage_norm_pool_head(h: torch.Tensor, g_final: torch.Tensor, eps: float, batch: DeviceBatch,
+                             w_head: torch.Tensor, b_head: float, pool: int, tau: float, want_hidden=True, stream=None):
+    _dev(h, torch.float32), _dev(g_final, torch.float32), _dev(w_head, torch.float32)
+    T, d = h.shape
+    hidden = torch.empty(T, d, dtype=torch.bfloat16, device=h.device) if want_hidden else None
+    scores = torch.empty(batch.batch, dtype=torch.float32, device=h.device)
+    esc = torch.empty(batch.batch, dtype=torch.uint8, device=h.device)
+    ws = torch.empty(max(4 * T, 256), dtype=torch.uint8, device=h.device)
+    _check(load_library().arb_stage_norm_pool_head(_ptr(h), _ptr(g_final), float(eps), C.byref(batch.c), d,
+                                                   _ptr(w_head), float(b_head), pool, float(tau), _ptr(hidden),
+                                                   _ptr(scores), _ptr(esc), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return scores, esc, hidden
+
+
+class StageTimer:
+    """HIP events the library records around every launch of one stage of the
+    forward (arb_model_trace), on the stream the kernels run on."""
+
+    def __init__(self, model: Model, stage: int, capacity: int):
+        self.model, self.stage, self.n = model, stage, capacity
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.start, self.stop = (C.c_void_p * capacity)(), (C.c_void_p * capacity)()
+        for arr in (self.start, self.stop):
+            for i in range(capacity):
+                ev = C.c_void_p()
+                if self.hip.hipEventCreate(C.byref(ev)) != 0:
+                    raise RuntimeError("hipEventCreate failed")
+                arr[i] = ev
+
+    def arm(self):
+        _check(load_library().arb_model_trace(self.model.handle, self.stage, self.start, self.stop, self.n))
+
+    def disarm(self):
+        count = load_library().arb_model_trace_count(self.model.handle)
+        _check(load_library().arb_model_trace(self.model.handle, self.stage, None, None, 0))
+        return count
+
+    def durations_ms(self, count: int):
+        """Per-launch durations; call after the stream has been synchronised."""
+        out = []
+        for i in range(count):
+            ms = C.c_float()
+            if self.hip.hipEventElapsedTime(C.byref(ms), self.start[i], self.stop[i]) != 0:
+                raise RuntimeError("hipEventElapsedTime failed")
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for arr in (self.start, self.stop):
+            for i in range(self.n):
+                if arr[i]:
+                    self.hip.hipEventDestroy(arr[i])
+                    arr[i] = None

@@ -1,0 +1,390 @@
+// The C ABI of libarb (include/arb.h): argument validation, workspace carving
+// and the launch sequence of the step-scoring forward.  No allocation, no
+// synchronisation and no read-back happen in the hot calls.
+#include "common.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <new>
+#include <vector>
+
+// ------------------------------------------------------------------------- errors
+
+static thread_local char g_err[512] = "";
+
+arb_status arb_fail(arb_status st, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+extern "C" const char *arb_last_error(void) { return g_err; }
+
+// -------------------------------------------------------------------------- model
+
+struct arb_model {
+  arb_model_cfg cfg;
+  const bf16 *embed;
+  std::vector<const bf16 *> wqkv, wo, wgu, wd;
+  std::vector<const float *> g_attn, g_mlp;
+  const float *g_final, *w_head;
+  float b_head;
+  int trace_stage = -1, trace_cap = 0, trace_n = 0;      // timing hook (arb_model_trace)
+  std::vector<hipEvent_t> trace_start, trace_stop;
+  int qkv_rows() const { return (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim; }
+};
+
+extern "C" arb_status arb_model_create(const arb_model_cfg *cfg, const arb_weights *w, arb_model **out) {
+  if (!cfg || !w || !out) return arb_fail(ARB_EINVAL, "arb_model_create: null argument");
+  *out = nullptr;
+  const arb_model_cfg &c = *cfg;
+  if (c.n_layers <= 0 || c.d_model <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 ||
+      c.d_ffn <= 0 || c.vocab <= 0)
+    return arb_fail(ARB_ESHAPE, "arb_model_create: non-positive dimension");
+  if (c.n_q_heads % c.n_kv_heads != 0)
+    return arb_fail(ARB_ESHAPE, "arb_model_create: n_q_heads %d is not a multiple of n_kv_heads %d", c.n_q_heads,
+                    c.n_kv_heads);
+  if (c.head_dim % 2 != 0) return arb_fail(ARB_ESHAPE, "arb_model_create: odd head_dim %d", c.head_dim);
+  if (!(c.rms_eps >= 0.f) || !(c.rope_base > 0.f))
+    return arb_fail(ARB_EINVAL, "arb_model_create: rms_eps %g / rope_base %g", c.rms_eps, c.rope_base);
+  if (c.pool != ARB_POOL_MEAN && c.pool != ARB_POOL_LAST)
+    return arb_fail(ARB_EINVAL, "arb_model_create: pool mode %d", c.pool);
+  if (c.kv_block != ARB_KV_BLOCK) return arb_fail(ARB_EUNSUPPORTED, "arb_model_create: kv_block %d (16 only)", c.kv_block);
+  if (c.head_dim != 64 && c.head_dim != 128)
+    return arb_fail(ARB_EUNSUPPORTED, "arb_model_create: head_dim %d (64 or 128 only)", c.head_dim);
+  if (c.d_model % 128 != 0 || c.d_ffn % 128 != 0 || (c.n_q_heads * c.head_dim) % 128 != 0 || c.d_model > 8192)
+    return arb_fail(ARB_EUNSUPPORTED, "arb_model_create: d_model %d, d_ffn %d, n_q_heads*head_dim %d must be multiples of 128 (d_model <= 8192)",
+                    c.d_model, c.d_ffn, c.n_q_heads * c.head_dim);
+  if (((c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim) % 128 != 0)
+    return arb_fail(ARB_EUNSUPPORTED, "arb_model_create: (Hq + 2 Hkv) * head_dim must be a multiple of 128");
+  if (!w->embed || !w->wqkv || !w->wo || !w->wgu || !w->wd || !w->g_attn || !w->g_mlp || !w->g_final)
+    return arb_fail(ARB_EINVAL, "arb_model_create: null weight pointer");
+  if (c.has_router_head && !w->w_head) return arb_fail(ARB_EINVAL, "arb_model_create: has_router_head but w_head is null");
+  for (int l = 0; l < c.n_layers; ++l)
+    if (!w->wqkv[l] || !w->wo[l] || !w->wgu[l] || !w->wd[l] || !w->g_attn[l] || !w->g_mlp[l])
+      return arb_fail(ARB_EINVAL, "arb_model_create: null weight pointer in layer %d", l);
+  arb_model *m = new (std::nothrow) arb_model;
+  if (!m) return arb_fail(ARB_EINVAL, "arb_model_create: out of host memory");
+  m->cfg = c;
+  m->embed = (const bf16 *)w->embed;
+  for (int l = 0; l < c.n_layers; ++l) {
+    m->wqkv.push_back((const bf16 *)w->wqkv[l]);
+    m->wo.push_back((const bf16 *)w->wo[l]);
+    m->wgu.push_back((const bf16 *)w->wgu[l]);
+    m->wd.push_back((const bf16 *)w->wd[l]);
+    m->g_attn.push_back(w->g_attn[l]);
+    m->g_mlp.push_back(w->g_mlp[l]);
+  }
+  m->g_final = w->g_final;
+  m->w_head = c.has_router_head ? w->w_head : nullptr;
+  m->b_head = w->b_head;
+  *out = m;
+  return ARB_OK;
+}
+
+extern "C" arb_status arb_model_destroy(arb_model *m) {
+  delete m;
+  return ARB_OK;
+}
+
+extern "C" arb_status arb_model_trace(arb_model *m, int32_t stage, void *const *start, void *const *stop, int32_t n) {
+  if (!m || n < 0 || (n > 0 && (!start || !stop))) return arb_fail(ARB_EINVAL, "arb_model_trace: bad argument");
+  m->trace_stage = n > 0 ? stage : -1;
+  m->trace_cap = n;
+  m->trace_n = 0;
+  m->trace_start.assign((hipEvent_t const *)start, (hipEvent_t const *)start + n);
+  m->trace_stop.assign((hipEvent_t const *)stop, (hipEvent_t const *)stop + n);
+  return ARB_OK;
+}
+
+extern "C" int32_t arb_model_trace_count(const arb_model *m) { return m ? m->trace_n : 0; }
+
+// Brackets one launch with the caller's events when its stage is being traced.
+struct TraceScope {
+  arb_model *m;
+  hipStream_t st;
+  bool on;
+  TraceScope(arb_model *m_, int stage, hipStream_t st_) : m(m_), st(st_) {
+    on = m->trace_stage == stage && m->trace_n < m->trace_cap;
+    if (on) (void)hipEventRecord(m->trace_start[m->trace_n], st);
+  }
+  ~TraceScope() {
+    if (on) (void)hipEventRecord(m->trace_stop[m->trace_n++], st);
+  }
+};
+
+// ---------------------------------------------------------------------- workspace
+
+struct Workspace {
+  float *h;          // fp32 [T, d] residual stream
+  bf16 *x;           // bf16 [T, d] normed activations
+  bf16 *qkv;         // bf16 [T, (Hq+2Hkv)*hd]
+  bf16 *attn;        // bf16 [T, Hq*hd]
+  bf16 *act;         // bf16 [T, F]
+  int32_t *tok_pos, *tok_slot;
+  f32x2 *cs;         // [T, hd/2] rotary table
+  float *tok_dot;    // [T]
+  void *attn_ws;
+  size_t attn_ws_bytes, total;
+};
+
+static Workspace carve(const arb_model_cfg &c, int T, int max_ctx, void *base) {
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void *p = base ? (char *)base + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  const size_t t = (size_t)T;
+  w.h = (float *)take(t * c.d_model * sizeof(float));
+  w.x = (bf16 *)take(t * c.d_model * sizeof(bf16));
+  w.qkv = (bf16 *)take(t * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * sizeof(bf16));
+  w.attn = (bf16 *)take(t * c.n_q_heads * c.head_dim * sizeof(bf16));
+  w.act = (bf16 *)take(t * c.d_ffn * sizeof(bf16));
+  w.tok_pos = (int32_t *)take(t * sizeof(int32_t));
+  w.tok_slot = (int32_t *)take(t * sizeof(int32_t));
+  w.cs = (f32x2 *)take(t * (c.head_dim / 2) * sizeof(f32x2));
+  w.tok_dot = (float *)take(t * sizeof(float));
+  w.attn_ws_bytes = attention_ws_bytes(attention_splits_cap(max_ctx), T, c.n_q_heads, c.head_dim);
+  w.attn_ws = take(w.attn_ws_bytes);
+  w.total = off;
+  return w;
+}
+
+extern "C" size_t arb_workspace_bytes(const arb_model *m, int32_t max_batch, int32_t max_total_tokens,
+                                      int32_t max_ctx) {
+  if (!m || max_batch < 0 || max_total_tokens < 0 || max_ctx < 0) return 0;
+  return carve(m->cfg, max_total_tokens, max_ctx, nullptr).total;
+}
+
+// --------------------------------------------------------------- batch validation
+
+struct BatchInfo {
+  int max_ctx, max_step;
+};
+
+static arb_status check_batch(const arb_batch *bt, int kv_block, BatchInfo *info, bool need_tokens) {
+  if (!bt) return arb_fail(ARB_EINVAL, "null batch");
+  if (bt->batch < 0 || bt->total_tokens < 0 || bt->max_blocks_per_seq < 0)
+    return arb_fail(ARB_EINVAL, "negative batch size / token count / table width");
+  info->max_ctx = info->max_step = 0;
+  if (bt->batch == 0) {
+    if (bt->total_tokens != 0) return arb_fail(ARB_EINVAL, "empty batch with %d tokens", bt->total_tokens);
+    return ARB_OK;
+  }
+  if (!bt->block_tables || !bt->prefix_lens || !bt->cu_step_lens || !bt->prefix_lens_host || !bt->cu_step_lens_host ||
+      (need_tokens && !bt->token_ids))
+    return arb_fail(ARB_EINVAL, "null pointer in batch");
+  const int32_t *cu = bt->cu_step_lens_host, *p = bt->prefix_lens_host;
+  if (cu[0] != 0) return arb_fail(ARB_EINVAL, "cu_step_lens[0] = %d, expected 0", cu[0]);
+  for (int b = 0; b < bt->batch; ++b) {
+    const long long s = (long long)cu[b + 1] - cu[b];
+    if (s < 1) return arb_fail(ARB_EINVAL, "sequence %d has a step of %lld tokens (need >= 1)", b, s);
+    if (p[b] < 0) return arb_fail(ARB_EINVAL, "sequence %d has prefix length %d", b, p[b]);
+    const long long ctx = (long long)p[b] + s;
+    if (ctx > (1 << 30)) return arb_fail(ARB_ECAPACITY, "sequence %d: context of %lld tokens", b, ctx);
+    if ((ctx + kv_block - 1) / kv_block > bt->max_blocks_per_seq)
+      return arb_fail(ARB_ECAPACITY, "sequence %d needs %lld blocks, table rows hold %d", b,
+                      (ctx + kv_block - 1) / kv_block, bt->max_blocks_per_seq);
+    if (ctx > info->max_ctx) info->max_ctx = (int)ctx;
+    if (s > info->max_step) info->max_step = (int)s;
+  }
+  if (cu[bt->batch] != bt->total_tokens)
+    return arb_fail(ARB_EINVAL, "cu_step_lens[batch] = %d but total_tokens = %d", cu[bt->batch], bt->total_tokens);
+  return ARB_OK;
+}
+
+// ------------------------------------------------------------------------ forward
+
+static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, bool with_head, float tau,
+                          float *scores, uint8_t *escalate, void *hidden_out, void *ws, size_t ws_bytes,
+                          hipStream_t st) {
+  if (!m || !kv) return arb_fail(ARB_EINVAL, "null model or kv");
+  const arb_model_cfg &c = m->cfg;
+  BatchInfo info;
+  if (arb_status s = check_batch(bt, c.kv_block, &info, true)) return s;
+  if (bt->batch == 0) return ARB_OK;
+  if (with_head && !scores) return arb_fail(ARB_EINVAL, "model has a router head but scores is null");
+  if (!with_head && (scores || escalate)) return arb_fail(ARB_EINVAL, "scores/escalate given but no router head is applied");
+  if (!kv->k_pool || !kv->v_pool) return arb_fail(ARB_EINVAL, "null kv pool table");
+  for (int l = 0; l < c.n_layers; ++l)
+    if (!kv->k_pool[l] || !kv->v_pool[l]) return arb_fail(ARB_EINVAL, "null kv pool in layer %d", l);
+  const int T = bt->total_tokens, B = bt->batch, d = c.d_model;
+  const Workspace w = carve(c, T, info.max_ctx, ws);
+  if (!ws || ws_bytes < w.total) return arb_fail(ARB_ECAPACITY, "workspace %zu < %zu bytes", ws_bytes, w.total);
+
+  const int G = c.n_q_heads / c.n_kv_heads;
+  const AttnPlan plan = plan_attention(B, bt->prefix_lens_host, bt->cu_step_lens_host, G, c.n_kv_heads);
+
+  arb_status s;
+  if ((s = launch_token_meta(bt->prefix_lens, bt->cu_step_lens, bt->block_tables, B, T, bt->max_blocks_per_seq,
+                             c.kv_block, w.tok_pos, w.tok_slot, st)))
+    return s;
+  if ((s = launch_rope_table(w.tok_pos, T, c.head_dim, c.rope_base, w.cs, st))) return s;
+  for (int l = 0; l < c.n_layers; ++l) {
+    {
+      TraceScope t(m, ARB_STAGE_NORM, st);
+      if (l == 0)
+        s = launch_embed_rmsnorm(m->embed, bt->token_ids, m->g_attn[0], c.rms_eps, T, d, w.h, w.x, st);
+      else
+        s = launch_rmsnorm(w.h, m->g_attn[l], c.rms_eps, T, d, w.x, st);
+    }
+    if (s) return s;
+    {
+      TraceScope t(m, ARB_STAGE_QKV, st);
+      s = launch_gemm(w.x, m->wqkv[l], w.qkv, T, m->qkv_rows(), d, ARB_EPI_STORE_BF16, st);
+    }
+    if (s) return s;
+    {
+      TraceScope t(m, ARB_STAGE_ROPE_APPEND, st);
+      s = launch_rope_append(w.qkv, w.cs, w.tok_slot, (bf16 *)kv->k_pool[l], (bf16 *)kv->v_pool[l], T, c.n_q_heads,
+                             c.n_kv_heads, c.head_dim, st);
+    }
+    if (s) return s;
+    {
+      TraceScope t(m, ARB_STAGE_ATTENTION, st);
+      s = launch_attention(w.qkv, m->qkv_rows(), (const bf16 *)kv->k_pool[l], (const bf16 *)kv->v_pool[l],
+                           bt->block_tables, bt->max_blocks_per_seq, bt->prefix_lens, bt->cu_step_lens, B, T,
+                           c.n_q_heads, c.n_kv_heads, c.head_dim, plan, w.attn, w.attn_ws, w.attn_ws_bytes, st);
+    }
+    if (s) return s;
+    {
+      TraceScope t(m, ARB_STAGE_OPROJ, st);
+      s = launch_gemm(w.attn, m->wo[l], w.h, T, d, c.n_q_heads * c.head_dim, ARB_EPI_RESIDUAL_F32, st);
+    }
+    if (s) return s;
+    if ((s = launch_rmsnorm(w.h, m->g_mlp[l], c.rms_eps, T, d, w.x, st))) return s;
+    {
+      TraceScope t(m, ARB_STAGE_GATE_UP, st);
+      s = launch_gemm(w.x, m->wgu[l], w.act, T, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, st);
+    }
+    if (s) return s;
+    {
+      TraceScope t(m, ARB_STAGE_DOWN, st);
+      s = launch_gemm(w.act, m->wd[l], w.h, T, d, c.d_ffn, ARB_EPI_RESIDUAL_F32, st);
+    }
+    if (s) return s;
+  }
+  if ((s = launch_final_norm_head(w.h, m->g_final, c.rms_eps, T, d, with_head ? m->w_head : nullptr,
+                                  (bf16 *)hidden_out, with_head ? w.tok_dot : nullptr, st)))
+    return s;
+  if (with_head)
+    if ((s = launch_pool_route(w.tok_dot, bt->cu_step_lens, B, m->b_head, c.pool, tau, scores, escalate, st))) return s;
+  return ARB_OK;
+}
+
+extern "C" arb_status arb_score_steps(arb_model *m, const arb_kv *kv, const arb_batch *batch, float tau, float *scores,
+                                      uint8_t *escalate, void *hidden_out, void *ws, size_t ws_bytes, void *stream) {
+  if (!m) return arb_fail(ARB_EINVAL, "null model");
+  return forward(m, kv, batch, m->cfg.has_router_head != 0, tau, scores, escalate, hidden_out, ws, ws_bytes,
+                 (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_prefill(arb_model *m, const arb_kv *kv, const arb_batch *batch, void *hidden_out, void *ws,
+                                  size_t ws_bytes, void *stream) {
+  if (!m) return arb_fail(ARB_EINVAL, "null model");
+  return forward(m, kv, batch, false, 0.f, nullptr, nullptr, hidden_out, ws, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_route(const float *scores, int32_t n, float tau, int32_t sense, uint8_t *escalate,
+                                void *stream) {
+  if (n < 0) return arb_fail(ARB_EINVAL, "arb_route: n = %d", n);
+  if (n == 0) return ARB_OK;
+  if (!scores || !escalate) return arb_fail(ARB_EINVAL, "arb_route: null pointer");
+  if (sense != ARB_ESCALATE_IF_GT && sense != ARB_ACCEPT_IF_GT) return arb_fail(ARB_EINVAL, "arb_route: sense %d", sense);
+  return launch_route(scores, n, tau, sense, escalate, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream) {
+  BatchInfo info;
+  if (kv_block <= 0) return arb_fail(ARB_EINVAL, "arb_slot_mapping: kv_block %d", kv_block);
+  if (arb_status s = check_batch(batch, kv_block, &info, false)) return s;
+  if (batch->batch == 0) return ARB_OK;
+  if (!slots) return arb_fail(ARB_EINVAL, "arb_slot_mapping: null output");
+  return launch_token_meta(batch->prefix_lens, batch->cu_step_lens, batch->block_tables, batch->batch,
+                           batch->total_tokens, batch->max_blocks_per_seq, kv_block, nullptr, slots,
+                           (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------- stages
+
+extern "C" arb_status arb_stage_gemm(const void *A, const void *B, void *C, int32_t M, int32_t N, int32_t K,
+                                     int32_t epilogue, void *stream) {
+  if (M == 0) return ARB_OK;
+  if (!A || !B || !C) return arb_fail(ARB_EINVAL, "arb_stage_gemm: null pointer");
+  return launch_gemm((const bf16 *)A, (const bf16 *)B, C, M, N, K, epilogue, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, const void *k_pool,
+                                          const void *v_pool, const arb_batch *batch, void *out, void *ws,
+                                          size_t ws_bytes, void *stream) {
+  if (!m) return arb_fail(ARB_EINVAL, "null model");
+  const arb_model_cfg &c = m->cfg;
+  BatchInfo info;
+  if (arb_status s = check_batch(batch, c.kv_block, &info, false)) return s;
+  if (batch->batch == 0) return ARB_OK;
+  if (!q || !k_pool || !v_pool || !out) return arb_fail(ARB_EINVAL, "arb_stage_attention: null pointer");
+  if (q_row_stride < c.n_q_heads * c.head_dim || q_row_stride % 8 != 0)
+    return arb_fail(ARB_EINVAL, "arb_stage_attention: q_row_stride %d", q_row_stride);
+  const AttnPlan plan = plan_attention(batch->batch, batch->prefix_lens_host, batch->cu_step_lens_host,
+                                       c.n_q_heads / c.n_kv_heads, c.n_kv_heads);
+  return launch_attention((const bf16 *)q, q_row_stride, (const bf16 *)k_pool, (const bf16 *)v_pool,
+                          batch->block_tables, batch->max_blocks_per_seq, batch->prefix_lens, batch->cu_step_lens,
+                          batch->batch, batch->total_tokens, c.n_q_heads, c.n_kv_heads, c.head_dim, plan, (bf16 *)out,
+                          ws, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_stage_rmsnorm(const float *x, const float *g, float eps, int32_t T, int32_t d, void *out,
+                                        void *stream) {
+  if (T < 0) return arb_fail(ARB_EINVAL, "arb_stage_rmsnorm: T = %d", T);
+  if (T == 0) return ARB_OK;
+  if (!x || !g || !out) return arb_fail(ARB_EINVAL, "arb_stage_rmsnorm: null pointer");
+  return launch_rmsnorm(x, g, eps, T, d, (bf16 *)out, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_stage_rope_append(const arb_model *m, void *qkv, void *k_pool, void *v_pool,
+                                            const arb_batch *batch, void *ws, size_t ws_bytes, void *stream) {
+  if (!m) return arb_fail(ARB_EINVAL, "null model");
+  const arb_model_cfg &c = m->cfg;
+  BatchInfo info;
+  if (arb_status s = check_batch(batch, c.kv_block, &info, false)) return s;
+  if (batch->batch == 0) return ARB_OK;
+  if (!qkv || !k_pool || !v_pool) return arb_fail(ARB_EINVAL, "arb_stage_rope_append: null pointer");
+  const size_t T = batch->total_tokens;
+  const size_t need = 2 * align_up(T * sizeof(int32_t), 256) + align_up(T * (c.head_dim / 2) * sizeof(f32x2), 256);
+  if (!ws || ws_bytes < need) return arb_fail(ARB_ECAPACITY, "arb_stage_rope_append: workspace %zu < %zu bytes", ws_bytes, need);
+  int32_t *tok_pos = (int32_t *)ws;
+  int32_t *tok_slot = (int32_t *)((char *)ws + align_up(T * sizeof(int32_t), 256));
+  f32x2 *cs = (f32x2 *)((char *)ws + 2 * align_up(T * sizeof(int32_t), 256));
+  hipStream_t st = (hipStream_t)stream;
+  arb_status s;
+  if ((s = launch_token_meta(batch->prefix_lens, batch->cu_step_lens, batch->block_tables, batch->batch, (int)T,
+                             batch->max_blocks_per_seq, c.kv_block, tok_pos, tok_slot, st)))
+    return s;
+  if ((s = launch_rope_table(tok_pos, (int)T, c.head_dim, c.rope_base, cs, st))) return s;
+  return launch_rope_append((bf16 *)qkv, cs, tok_slot, (bf16 *)k_pool, (bf16 *)v_pool, (int)T, c.n_q_heads,
+                            c.n_kv_heads, c.head_dim, st);
+}
+
+extern "C" arb_status arb_stage_norm_pool_head(const float *h, const float *g_final, float eps, const arb_batch *batch,
+                                               int32_t d, const float *w_head, float b_head, int32_t pool, float tau,
+                                               void *hidden_out, float *scores, uint8_t *escalate, void *ws,
+                                               size_t ws_bytes, void *stream) {
+  BatchInfo info;
+  if (arb_status s = check_batch(batch, ARB_KV_BLOCK, &info, false)) return s;
+  if (batch->batch == 0) return ARB_OK;
+  if (!h || !g_final || !w_head || !scores) return arb_fail(ARB_EINVAL, "arb_stage_norm_pool_head: null pointer");
+  if (pool != ARB_POOL_MEAN && pool != ARB_POOL_LAST) return arb_fail(ARB_EINVAL, "arb_stage_norm_pool_head: pool %d", pool);
+  const size_t need = (size_t)batch->total_tokens * sizeof(float);
+  if (!ws || ws_bytes < need) return arb_fail(ARB_ECAPACITY, "arb_stage_norm_pool_head: workspace %zu < %zu bytes", ws_bytes, need);
+  hipStream_t st = (hipStream_t)stream;
+  if (arb_status s = launch_final_norm_head(h, g_final, eps, batch->total_tokens, d, w_head, (bf16 *)hidden_out,
+                                            (float *)ws, st))
+    return s;
+  return launch_pool_route((const float *)ws, batch->cu_step_lens, batch->batch, b_head, pool, tau, scores, escalate, st);
+}

@@ -1,0 +1,335 @@
+// Ragged GQA append-attention over a block-paged bf16 KV cache.
+//
+// Work decomposition.  For sequence b and kv head hk, the G = Hq/Hkv query heads
+// that share hk and the s_b step tokens form s_b*G query rows (row = i*G + g,
+// token-major).  A workgroup of 4 waves takes 128 rows (32 per wave) and one
+// chunk of the key range ("split"); chunks of a sequence are merged afterwards
+// from their online-softmax states (m, l, unnormalised acc).  Every KV byte is
+// streamed from HBM once per 128 rows that need it; rows of different query
+// tiles of the same (b, hk) meet in L2.
+//
+// Per 64-key tile: K goes to LDS row-major [key][hd] (XOR-swizzled 16-byte
+// chunks), V goes to LDS transposed [hd][key] so that both MFMA operands are
+// contiguous reads.  S^T = K Q^T (keys are MFMA rows, queries are columns), so a
+// lane owns one query column: the row max / row sum are in-lane reductions plus
+// one cross-half shuffle, and exp2(S^T - m) is already laid out as the B operand
+// of O^T = V^T P^T.  The pairing of MFMA contraction slots with keys follows the
+// 32x32 D layout (lane half h, registers 8u..8u+7 of tile t hold keys
+// 32t+16u+4h+{0..3} and 32t+16u+8+4h+{0..3}); V^T fragments are read with the
+// same pairing.
+#include "common.h"
+
+#include <math.h>
+
+namespace {
+
+constexpr int QROWS = 128;     // query rows per workgroup
+constexpr int KT = 64;         // keys per tile
+constexpr int VT_STRIDE = KT + 4;   // elements; keeps 8-byte alignment and spreads banks
+
+template <int HD>
+struct Smem {
+  __attribute__((aligned(16))) bf16 k[KT * HD];
+  __attribute__((aligned(16))) bf16 vt[HD * VT_STRIDE];
+};
+
+template <int HD>
+__device__ __forceinline__ int k_off(int key, int chunk) {   // 16-byte chunk within a key row
+  return key * HD + ((chunk ^ (key & 7)) << 3);
+}
+
+template <int HD, bool SPLIT>
+__global__ __launch_bounds__(256) void attention_kernel(
+    const bf16 *__restrict__ q, int q_row_stride, const bf16 *__restrict__ k_pool, const bf16 *__restrict__ v_pool,
+    const int32_t *__restrict__ block_tables, int max_blocks, const int32_t *__restrict__ prefix_lens,
+    const int32_t *__restrict__ cu, int T, int Hq, int Hkv, int max_qtiles, int kv_chunk, float scale_log2,
+    bf16 *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml) {
+  constexpr int CPK = HD / 8;              // 16-byte chunks per key
+  constexpr int LOADS = KT * CPK / 256;    // chunks per thread per operand per tile
+  constexpr int KSTEPS = HD / 16;          // MFMA k-steps over the head dimension
+  constexpr int MT = HD / 32;              // 32-row tiles of O^T
+  __shared__ Smem<HD> sm;
+
+  const int split = blockIdx.x, b = blockIdx.z;
+  const int hk = blockIdx.y / max_qtiles, qtile = blockIdx.y - hk * max_qtiles;
+  const int G = Hq / Hkv;
+  const int p = prefix_lens[b], tok0 = cu[b], s = cu[b + 1] - tok0;
+  const int rows = s * G, row0 = qtile * QROWS;
+  if (row0 >= rows) return;
+  const int last_row = min(rows, row0 + QROWS) - 1;
+  const int visible = p + last_row / G + 1;            // keys any row of this tile may see
+  const int kv_begin = split * kv_chunk;
+  if (kv_begin >= visible) return;
+  const int kv_end = min(visible, kv_begin + kv_chunk);
+  const int ctx = p + s;
+  const int n_blk = (ctx + ARB_KV_BLOCK - 1) / ARB_KV_BLOCK;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+
+  // this lane's query row
+  const int row = row0 + wave * 32 + col;
+  const bool row_ok = row < rows;
+  const int tok_i = row_ok ? row / G : 0;
+  const int head = hk * G + (row_ok ? row - tok_i * G : 0);
+  const int limit = p + tok_i;                         // last visible key (inclusive)
+
+  bf16x8 qf[KSTEPS];
+  {
+    const bf16 *qrow = q + (size_t)(tok0 + tok_i) * q_row_stride + head * HD;
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      if (row_ok) {
+        qf[kk] = *(const bf16x8 *)(qrow + kk * 16 + half * 8);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[kk][e] = (bf16)0.f;
+      }
+    }
+  }
+
+  f32x16 o[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[mt][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int32_t *table = block_tables + (size_t)b * max_blocks;
+  u32x4 rk[LOADS], rv[LOADS];
+
+  auto load_tile = [&](int tile_start) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int c = tid + 256 * i, key = c / CPK, chunk = c - key * CPK;
+      const int j = tile_start + key, bi = j / ARB_KV_BLOCK;
+      if (bi < n_blk) {
+        const size_t base = (((size_t)table[bi] * Hkv + hk) * ARB_KV_BLOCK + (j % ARB_KV_BLOCK)) * HD + chunk * 8;
+        rk[i] = *(const u32x4 *)(k_pool + base);
+        rv[i] = j < ctx ? *(const u32x4 *)(v_pool + base) : u32x4{0, 0, 0, 0};
+      } else {
+        rk[i] = u32x4{0, 0, 0, 0};
+        rv[i] = u32x4{0, 0, 0, 0};
+      }
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int c = tid + 256 * i, key = c / CPK, chunk = c - key * CPK;
+      *(u32x4 *)&sm.k[k_off<HD>(key, chunk)] = rk[i];
+      const bf16 *ve = (const bf16 *)&rv[i];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sm.vt[(chunk * 8 + e) * VT_STRIDE + key] = ve[e];
+    }
+  };
+
+  load_tile(kv_begin);
+  for (int ts = kv_begin; ts < kv_end; ts += KT) {
+    __syncthreads();                 // previous tile's reads are done
+    store_tile();
+    __syncthreads();
+    if (ts + KT < kv_end) load_tile(ts + KT);
+
+    // S^T tile: 64 keys x 32 queries per wave
+    f32x16 st[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        const bf16x8 kf = *(const bf16x8 *)&sm.k[k_off<HD>(t * 32 + col, kk * 2 + half)];
+        st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
+      }
+    }
+    // scale, mask, running max
+    float m_new = m_run;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = ts + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const float v = j <= limit ? st[t][r] * scale_log2 : -INFINITY;
+        st[t][r] = v;
+        m_new = fmaxf(m_new, v);
+      }
+    m_new = fmaxf(m_new, __shfl_xor(m_new, 32, 64));
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = exp2f(m_run - m_use);          // m_run = -inf -> 0
+    m_run = m_new;
+    float l_add = 0.f;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pv = exp2f(st[t][r] - m_use);
+        l_add += pv;
+        pf[t][r >> 3][r & 7] = (bf16)pv;
+      }
+    l_run = l_run * alpha + l_add;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[mt][r] *= alpha;
+    // O^T += V^T P^T
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int kbase = t * 32 + u * 16 + 4 * half;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const bf16 *vrow = &sm.vt[(mt * 32 + col) * VT_STRIDE + kbase];
+          const bf16x4 lo = *(const bf16x4 *)vrow, hi = *(const bf16x4 *)(vrow + 8);
+          const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][u], o[mt], 0, 0, 0);
+        }
+      }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (!row_ok) return;
+  const size_t orow = (size_t)(tok0 + tok_i) * Hq + head;   // (token, head) index
+  if (!SPLIT) {
+    const float inv = 1.0f / l_tot;
+    bf16 *dst = out + orow * HD;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[mt][r4 * 4 + e] * inv);
+        *(bf16x4 *)(dst + mt * 32 + 8 * r4 + 4 * half) = v;
+      }
+  } else {
+    float *dst = part_acc + ((size_t)split * T * Hq + orow) * HD;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4)
+        *(f32x4 *)(dst + mt * 32 + 8 * r4 + 4 * half) =
+            f32x4{o[mt][r4 * 4], o[mt][r4 * 4 + 1], o[mt][r4 * 4 + 2], o[mt][r4 * 4 + 3]};
+    if (half == 0) {
+      float *ml = part_ml + ((size_t)split * T * Hq + orow) * 2;
+      ml[0] = m_run;
+      ml[1] = l_tot;
+    }
+  }
+}
+
+// Merge of the split partials: out = sum_s w_s acc_s / sum_s w_s l_s with
+// w_s = exp2(m_s - max_s m_s).  One wave per (token, head).
+template <int HD>
+__global__ __launch_bounds__(64) void attention_merge_kernel(const float *__restrict__ part_acc,
+                                                             const float *__restrict__ part_ml,
+                                                             const int32_t *__restrict__ tok_pos, int T, int Hq,
+                                                             int kv_chunk, bf16 *__restrict__ out) {
+  const int idx = blockIdx.x;             // token * Hq + head
+  const int tok = idx / Hq;
+  const int n_splits = tok_pos[tok] / kv_chunk + 1;      // splits that start at or before this token's position
+  const size_t stride = (size_t)T * Hq;
+  float m = -INFINITY;
+  for (int sidx = 0; sidx < n_splits; ++sidx) m = fmaxf(m, part_ml[(sidx * stride + idx) * 2]);
+  constexpr int PER = HD / 64;
+  float acc[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+  float l = 0.f;
+  for (int sidx = 0; sidx < n_splits; ++sidx) {
+    const float ms = part_ml[(sidx * stride + idx) * 2];
+    if (ms == -INFINITY) continue;
+    const float w = exp2f(ms - m);
+    l += w * part_ml[(sidx * stride + idx) * 2 + 1];
+    const float *src = part_acc + (sidx * stride + idx) * HD + threadIdx.x * PER;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) acc[e] += w * src[e];
+  }
+  const float inv = 1.0f / l;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) out[(size_t)idx * HD + threadIdx.x * PER + e] = (bf16)(acc[e] * inv);
+}
+
+}  // namespace
+
+static const int kTargetWorkgroups = 1024;   // ~4 per CU on 256 CUs
+static const int kMinChunk = 256, kMaxSplits = 64;
+
+int attention_splits_cap(int max_ctx) {
+  if (max_ctx <= 0) return 1;
+  const int n = ceil_div(max_ctx, kMinChunk);
+  return n < kMaxSplits ? n : kMaxSplits;
+}
+
+AttnPlan plan_attention(int batch, const int32_t *prefix_host, const int32_t *cu_host, int G, int n_kv_heads) {
+  long long keys_streamed = 0;          // sum over (sequence, kv head, query tile) of the context length
+  int max_ctx = 0, max_step = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int s = cu_host[b + 1] - cu_host[b], ctx = prefix_host[b] + s;
+    keys_streamed += (long long)ceil_div(s * G, QROWS) * n_kv_heads * ctx;
+    max_ctx = ctx > max_ctx ? ctx : max_ctx;
+    max_step = s > max_step ? s : max_step;
+  }
+  // keys per split so that about kTargetWorkgroups workgroups share the streaming evenly
+  long long chunk = (keys_streamed / kTargetWorkgroups + KT - 1) / KT * KT;
+  if (chunk < kMinChunk) chunk = kMinChunk;
+  while (max_ctx > chunk * kMaxSplits) chunk += KT;
+  AttnPlan pl;
+  pl.max_qtiles = ceil_div(max_step * G, QROWS);
+  pl.kv_chunk = (int)chunk;
+  pl.max_splits = max_ctx > 0 ? ceil_div(max_ctx, pl.kv_chunk) : 1;
+  return pl;
+}
+
+size_t attention_ws_bytes(int max_splits_cap, int total_tokens, int n_q_heads, int head_dim) {
+  const size_t rows = (size_t)max_splits_cap * total_tokens * n_q_heads;
+  return align_up(rows * head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256) +
+         align_up((size_t)total_tokens * sizeof(int32_t), 256);
+}
+
+arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool, const bf16 *v_pool,
+                            const int32_t *block_tables, int max_blocks_per_seq, const int32_t *prefix_lens,
+                            const int32_t *cu_step_lens, int batch, int total_tokens, int n_q_heads, int n_kv_heads,
+                            int head_dim, const AttnPlan &plan, bf16 *out, void *ws, size_t ws_bytes, hipStream_t st) {
+  if (batch == 0 || total_tokens == 0) return ARB_OK;
+  if (head_dim != 64 && head_dim != 128) return arb_fail(ARB_EUNSUPPORTED, "attention: head_dim %d", head_dim);
+  const bool split = plan.max_splits > 1;
+  float *part_acc = nullptr, *part_ml = nullptr;
+  int32_t *tok_pos = nullptr;
+  if (split) {
+    const size_t need = attention_ws_bytes(plan.max_splits, total_tokens, n_q_heads, head_dim);
+    if (ws == nullptr || ws_bytes < need)
+      return arb_fail(ARB_ECAPACITY, "attention: workspace %zu < %zu bytes", ws_bytes, need);
+    const size_t rows = (size_t)plan.max_splits * total_tokens * n_q_heads;
+    char *pws = (char *)ws;
+    part_acc = (float *)pws; pws += align_up(rows * head_dim * sizeof(float), 256);
+    part_ml = (float *)pws;  pws += align_up(rows * 2 * sizeof(float), 256);
+    tok_pos = (int32_t *)pws;
+    if (arb_status s = launch_token_meta(prefix_lens, cu_step_lens, block_tables, batch, total_tokens,
+                                         max_blocks_per_seq, ARB_KV_BLOCK, tok_pos, nullptr, st))
+      return s;
+  }
+  const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)head_dim));
+  const dim3 grid(plan.max_splits, n_kv_heads * plan.max_qtiles, batch), block(256);
+#define ARB_ATTN_LAUNCH(HD, SPLIT)                                                                                 \
+  hipLaunchKernelGGL((attention_kernel<HD, SPLIT>), grid, block, 0, st, q, q_row_stride, k_pool, v_pool,           \
+                     block_tables, max_blocks_per_seq, prefix_lens, cu_step_lens, total_tokens, n_q_heads,         \
+                     n_kv_heads, plan.max_qtiles, plan.kv_chunk, scale_log2, out, part_acc, part_ml)
+  if (head_dim == 128) { if (split) ARB_ATTN_LAUNCH(128, true); else ARB_ATTN_LAUNCH(128, false); }
+  else                 { if (split) ARB_ATTN_LAUNCH(64, true);  else ARB_ATTN_LAUNCH(64, false); }
+#undef ARB_ATTN_LAUNCH
+  ARB_CHECK_LAUNCH("attention");
+  if (split) {
+    const dim3 mgrid(total_tokens * n_q_heads), mblock(64);
+    if (head_dim == 128)
+      hipLaunchKernelGGL((attention_merge_kernel<128>), mgrid, mblock, 0, st, part_acc, part_ml, tok_pos, total_tokens,
+                         n_q_heads, plan.kv_chunk, out);
+    else
+      hipLaunchKernelGGL((attention_merge_kernel<64>), mgrid, mblock, 0, st, part_acc, part_ml, tok_pos, total_tokens,
+                         n_q_heads, plan.kv_chunk, out);
+    ARB_CHECK_LAUNCH("attention_merge");
+  }
+  return ARB_OK;
+}

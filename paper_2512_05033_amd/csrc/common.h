@@ -1,0 +1,75 @@
+// Internal declarations shared by the libarb translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "arb.h"
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define ARB_WAVE 64
+#define ARB_KV_BLOCK 16
+
+// Records a message for arb_last_error() and returns `st`.
+arb_status arb_fail(arb_status st, const char *fmt, ...);
+
+#define ARB_CHECK_HIP(expr)                                                               \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) return arb_fail(ARB_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+#define ARB_CHECK_LAUNCH(name)                                                            \
+  do {                                                                                    \
+    hipError_t e_ = hipGetLastError();                                                    \
+    if (e_ != hipSuccess) return arb_fail(ARB_EHIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+  } while (0)
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
+
+// gemm.hip
+arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st);
+
+// attention.hip
+struct AttnPlan {
+  int kv_chunk;      // keys per split (multiple of 64)
+  int max_splits;    // ceil(max_ctx / kv_chunk) over the batch
+  int max_qtiles;    // ceil(max_step * G / 128)
+};
+AttnPlan plan_attention(int batch, const int32_t *prefix_host, const int32_t *cu_host, int G, int n_kv_heads);
+size_t attention_ws_bytes(int max_splits_cap, int total_tokens, int n_q_heads, int head_dim);
+int attention_splits_cap(int max_ctx);   // largest max_splits plan_attention can return for contexts <= max_ctx
+arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool, const bf16 *v_pool,
+                            const int32_t *block_tables, int max_blocks_per_seq, const int32_t *prefix_lens,
+                            const int32_t *cu_step_lens, int batch, int total_tokens, int n_q_heads, int n_kv_heads,
+                            int head_dim, const AttnPlan &plan, bf16 *out, void *ws, size_t ws_bytes, hipStream_t st);
+
+// elementwise.hip
+arb_status launch_token_meta(const int32_t *prefix_lens, const int32_t *cu_step_lens, const int32_t *block_tables,
+                             int batch, int total_tokens, int max_blocks_per_seq, int kv_block, int32_t *tok_pos,
+                             int32_t *tok_slot, hipStream_t st);
+arb_status launch_rope_table(const int32_t *tok_pos, int total_tokens, int head_dim, float rope_base, f32x2 *cs,
+                             hipStream_t st);
+arb_status launch_embed_rmsnorm(const bf16 *embed, const int32_t *token_ids, const float *g, float eps, int T, int d,
+                                float *h, bf16 *x, hipStream_t st);
+arb_status launch_rmsnorm(const float *h, const float *g, float eps, int T, int d, bf16 *x, hipStream_t st);
+arb_status launch_rope_append(bf16 *qkv, const f32x2 *cs, const int32_t *tok_slot, bf16 *k_pool, bf16 *v_pool, int T,
+                              int n_q_heads, int n_kv_heads, int head_dim, hipStream_t st);
+arb_status launch_final_norm_head(const float *h, const float *g, float eps, int T, int d, const float *w_head,
+                                  bf16 *hidden_out, float *tok_dot, hipStream_t st);
+arb_status launch_pool_route(const float *tok_dot, const int32_t *cu_step_lens, int batch, float b_head, int pool,
+                             float tau, float *scores, uint8_t *escalate, hipStream_t st);
+arb_status launch_route(const float *scores, int n, float tau, int sense, uint8_t *escalate, hipStream_t st);

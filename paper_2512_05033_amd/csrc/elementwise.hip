@@ -1,0 +1,281 @@
+// Row-wise and per-token kernels of the step-scoring forward: token metadata
+// (position, pool slot), rotary table, embedding gather + RMSNorm, RMSNorm,
+// rotary embedding + KV append, final RMSNorm + head dot, segmented pooling +
+// threshold.  All are HBM-bound and touch T*d elements a handful of times.
+#include "common.h"
+
+// ------------------------------------------------------------------ reductions
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Sum over a block of 256 threads; every thread gets the result.
+__device__ __forceinline__ float block_sum_256(float v, float *lds4) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) lds4[w] = v;
+  __syncthreads();
+  return lds4[0] + lds4[1] + lds4[2] + lds4[3];
+}
+
+// ---------------------------------------------------------------- token metadata
+
+// For step token j of sequence b at position pos = p_b + i:
+//   slot = block_tables[b][pos / blk] * blk + pos % blk.
+__global__ void token_meta_kernel(const int32_t *__restrict__ prefix_lens, const int32_t *__restrict__ cu,
+                                  const int32_t *__restrict__ tables, int batch, int T, int max_blocks, int blk,
+                                  int32_t *__restrict__ tok_pos, int32_t *__restrict__ tok_slot) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= T) return;
+  int lo = 0, hi = batch;                 // largest b with cu[b] <= j
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= j) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  const int pos = prefix_lens[b] + (j - cu[b]);
+  if (tok_pos) tok_pos[j] = pos;
+  if (tok_slot) tok_slot[j] = tables[(size_t)b * max_blocks + pos / blk] * blk + pos % blk;
+}
+
+arb_status launch_token_meta(const int32_t *prefix_lens, const int32_t *cu_step_lens, const int32_t *block_tables,
+                             int batch, int total_tokens, int max_blocks_per_seq, int kv_block, int32_t *tok_pos,
+                             int32_t *tok_slot, hipStream_t st) {
+  if (total_tokens == 0) return ARB_OK;
+  hipLaunchKernelGGL(token_meta_kernel, dim3(ceil_div(total_tokens, 256)), dim3(256), 0, st, prefix_lens,
+                     cu_step_lens, block_tables, batch, total_tokens, max_blocks_per_seq, kv_block, tok_pos, tok_slot);
+  ARB_CHECK_LAUNCH("token_meta");
+  return ARB_OK;
+}
+
+// -------------------------------------------------------------------- rotary table
+
+// cs[j][t] = (cos, sin) of pos_j * base^(-2t/hd), evaluated in fp64 so that the
+// fp32 table is correctly rounded even at positions of tens of thousands.
+__global__ void rope_table_kernel(const int32_t *__restrict__ tok_pos, int T, int half, double log2_base,
+                                  f32x2 *__restrict__ cs) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= T * half) return;
+  const int j = idx / half, t = idx - j * half;
+  const double inv_freq = exp2(-(double)t / (double)half * log2_base);
+  const double ang = (double)tok_pos[j] * inv_freq;
+  double s, c;
+  sincos(ang, &s, &c);
+  cs[idx] = f32x2{(float)c, (float)s};
+}
+
+arb_status launch_rope_table(const int32_t *tok_pos, int total_tokens, int head_dim, float rope_base, f32x2 *cs,
+                             hipStream_t st) {
+  const int half = head_dim / 2, n = total_tokens * half;
+  if (n == 0) return ARB_OK;
+  hipLaunchKernelGGL(rope_table_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, tok_pos, total_tokens, half,
+                     log2((double)rope_base), cs);
+  ARB_CHECK_LAUNCH("rope_table");
+  return ARB_OK;
+}
+
+// ------------------------------------------------------------------------ RMSNorm
+
+// One block of 256 threads per row; a row is held in registers between the
+// sum-of-squares pass and the scaling pass (d <= 256*8*ROW_VECS).
+#define ROW_VECS 4
+
+template <bool EMBED, bool HEAD>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h_in, const bf16 *__restrict__ embed,
+                                                      const int32_t *__restrict__ token_ids,
+                                                      const float *__restrict__ g, float eps, int d,
+                                                      float *__restrict__ h_out, bf16 *__restrict__ x_out,
+                                                      const float *__restrict__ w_head, float *__restrict__ tok_dot) {
+  __shared__ float red[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  float v[ROW_VECS][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < ROW_VECS; ++it) {
+    const int c = (it * 256 + tid) * 8;
+    if (c < d) {
+      if (EMBED) {
+        const bf16x8 e = *(const bf16x8 *)(embed + (size_t)token_ids[row] * d + c);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[it][k] = (float)e[k];
+        float *dst = h_out + (size_t)row * d + c;
+        *(f32x4 *)dst = f32x4{v[it][0], v[it][1], v[it][2], v[it][3]};
+        *(f32x4 *)(dst + 4) = f32x4{v[it][4], v[it][5], v[it][6], v[it][7]};
+      } else {
+        const float *src = h_in + (size_t)row * d + c;
+        const f32x4 a = *(const f32x4 *)src, b = *(const f32x4 *)(src + 4);
+        v[it][0] = a[0]; v[it][1] = a[1]; v[it][2] = a[2]; v[it][3] = a[3];
+        v[it][4] = b[0]; v[it][5] = b[1]; v[it][6] = b[2]; v[it][7] = b[3];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ss += v[it][k] * v[it][k];
+    }
+  }
+  ss = block_sum_256(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  float dot = 0.f;
+#pragma unroll
+  for (int it = 0; it < ROW_VECS; ++it) {
+    const int c = (it * 256 + tid) * 8;
+    if (c < d) {
+      const f32x4 g0 = *(const f32x4 *)(g + c), g1 = *(const f32x4 *)(g + c + 4);
+      float y[8];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { y[k] = v[it][k] * r * g0[k]; y[4 + k] = v[it][4 + k] * r * g1[k]; }
+      if (HEAD && w_head) {
+        const f32x4 w0 = *(const f32x4 *)(w_head + c), w1 = *(const f32x4 *)(w_head + c + 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dot += y[k] * w0[k] + y[4 + k] * w1[k];
+      }
+      if (x_out) {
+        bf16x8 o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) o[k] = (bf16)y[k];
+        *(bf16x8 *)(x_out + (size_t)row * d + c) = o;
+      }
+    }
+  }
+  if (HEAD && tok_dot) {
+    dot = block_sum_256(dot, red);
+    if (tid == 0) tok_dot[row] = dot;
+  }
+}
+
+static arb_status check_row_width(int d) {
+  if (d <= 0 || d % 8 != 0 || d > 256 * 8 * ROW_VECS)
+    return arb_fail(ARB_EUNSUPPORTED, "row width %d: need a multiple of 8 up to %d", d, 256 * 8 * ROW_VECS);
+  return ARB_OK;
+}
+
+arb_status launch_embed_rmsnorm(const bf16 *embed, const int32_t *token_ids, const float *g, float eps, int T, int d,
+                                float *h, bf16 *x, hipStream_t st) {
+  if (T == 0) return ARB_OK;
+  if (arb_status s = check_row_width(d)) return s;
+  hipLaunchKernelGGL((rmsnorm_kernel<true, false>), dim3(T), dim3(256), 0, st, (const float *)nullptr, embed,
+                     token_ids, g, eps, d, h, x, (const float *)nullptr, (float *)nullptr);
+  ARB_CHECK_LAUNCH("embed_rmsnorm");
+  return ARB_OK;
+}
+
+arb_status launch_rmsnorm(const float *h, const float *g, float eps, int T, int d, bf16 *x, hipStream_t st) {
+  if (T == 0) return ARB_OK;
+  if (arb_status s = check_row_width(d)) return s;
+  hipLaunchKernelGGL((rmsnorm_kernel<false, false>), dim3(T), dim3(256), 0, st, h, (const bf16 *)nullptr,
+                     (const int32_t *)nullptr, g, eps, d, (float *)nullptr, x, (const float *)nullptr,
+                     (float *)nullptr);
+  ARB_CHECK_LAUNCH("rmsnorm");
+  return ARB_OK;
+}
+
+arb_status launch_final_norm_head(const float *h, const float *g, float eps, int T, int d, const float *w_head,
+                                  bf16 *hidden_out, float *tok_dot, hipStream_t st) {
+  if (T == 0) return ARB_OK;
+  if (arb_status s = check_row_width(d)) return s;
+  hipLaunchKernelGGL((rmsnorm_kernel<false, true>), dim3(T), dim3(256), 0, st, h, (const bf16 *)nullptr,
+                     (const int32_t *)nullptr, g, eps, d, (float *)nullptr, hidden_out, w_head, tok_dot);
+  ARB_CHECK_LAUNCH("final_norm_head");
+  return ARB_OK;
+}
+
+// ------------------------------------------------------- rotary embedding + KV append
+
+// One block per token.  A work unit is (head, two adjacent pair indices t, t+1):
+// it reads u[t..t+1] and u[t+half..t+half+1] of that head, rotates q and k heads
+// by the token's table row ((a, b) -> (a cos - b sin, b cos + a sin)), writes q
+// back in place and k, v (bf16) to the token's slot of the pool
+// [n_blocks, Hkv, 16, hd].
+__global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv, const f32x2 *__restrict__ cs,
+                                                          const int32_t *__restrict__ tok_slot,
+                                                          bf16 *__restrict__ k_pool, bf16 *__restrict__ v_pool,
+                                                          int Hq, int Hkv, int hd) {
+  const int j = blockIdx.x;
+  const int half = hd / 2, units_per_head = half / 2, n_heads = Hq + 2 * Hkv;
+  bf16 *row = qkv + (size_t)j * n_heads * hd;
+  const int slot = tok_slot[j];
+  const size_t blk = slot / ARB_KV_BLOCK, off = slot % ARB_KV_BLOCK;
+  for (int u = threadIdx.x; u < n_heads * units_per_head; u += blockDim.x) {
+    const int head = u / units_per_head, t = (u - head * units_per_head) * 2;
+    bf16 *src = row + head * hd;
+    const bf16x2 a = *(const bf16x2 *)(src + t), b = *(const bf16x2 *)(src + t + half);
+    bf16x2 oa = a, ob = b;
+    if (head < Hq + Hkv) {
+      const f32x2 cs0 = cs[(size_t)j * half + t], cs1 = cs[(size_t)j * half + t + 1];
+      oa[0] = (bf16)((float)a[0] * cs0[0] - (float)b[0] * cs0[1]);
+      ob[0] = (bf16)((float)b[0] * cs0[0] + (float)a[0] * cs0[1]);
+      oa[1] = (bf16)((float)a[1] * cs1[0] - (float)b[1] * cs1[1]);
+      ob[1] = (bf16)((float)b[1] * cs1[0] + (float)a[1] * cs1[1]);
+    }
+    bf16 *dst;
+    if (head < Hq) {
+      dst = src;
+    } else if (head < Hq + Hkv) {
+      dst = k_pool + ((blk * Hkv + (head - Hq)) * ARB_KV_BLOCK + off) * hd;
+    } else {
+      dst = v_pool + ((blk * Hkv + (head - Hq - Hkv)) * ARB_KV_BLOCK + off) * hd;
+    }
+    *(bf16x2 *)(dst + t) = oa;
+    *(bf16x2 *)(dst + t + half) = ob;
+  }
+}
+
+arb_status launch_rope_append(bf16 *qkv, const f32x2 *cs, const int32_t *tok_slot, bf16 *k_pool, bf16 *v_pool, int T,
+                              int n_q_heads, int n_kv_heads, int head_dim, hipStream_t st) {
+  if (T == 0) return ARB_OK;
+  hipLaunchKernelGGL(rope_append_kernel, dim3(T), dim3(256), 0, st, qkv, cs, tok_slot, k_pool, v_pool, n_q_heads,
+                     n_kv_heads, head_dim);
+  ARB_CHECK_LAUNCH("rope_append");
+  return ARB_OK;
+}
+
+// ------------------------------------------------------- pooling + head + threshold
+
+// One wave per sequence.  tok_dot[j] = w . y_j, so by linearity of the head
+// score_b = mean_j tok_dot[j] + c (mean pooling) or tok_dot[last] + c.
+// The sum runs in a fixed order, so repeated calls give identical bits.
+// Decision (Alg. 1): accept iff score <= tau, i.e. escalate = !(score <= tau).
+__global__ __launch_bounds__(64) void pool_route_kernel(const float *__restrict__ tok_dot,
+                                                        const int32_t *__restrict__ cu, float b_head, int pool,
+                                                        float tau, float *__restrict__ scores,
+                                                        uint8_t *__restrict__ escalate) {
+  const int b = blockIdx.x, lo = cu[b], hi = cu[b + 1];
+  float acc = 0.f;
+  if (pool == ARB_POOL_LAST) {
+    acc = tok_dot[hi - 1];
+  } else {
+    for (int j = lo + (int)threadIdx.x; j < hi; j += 64) acc += tok_dot[j];
+    acc = wave_sum(acc) / (float)(hi - lo);
+  }
+  const float score = acc + b_head;
+  if (threadIdx.x == 0) {
+    scores[b] = score;
+    if (escalate) escalate[b] = !(score <= tau);
+  }
+}
+
+arb_status launch_pool_route(const float *tok_dot, const int32_t *cu_step_lens, int batch, float b_head, int pool,
+                             float tau, float *scores, uint8_t *escalate, hipStream_t st) {
+  if (batch == 0) return ARB_OK;
+  hipLaunchKernelGGL(pool_route_kernel, dim3(batch), dim3(64), 0, st, tok_dot, cu_step_lens, b_head, pool, tau, scores,
+                     escalate);
+  ARB_CHECK_LAUNCH("pool_route");
+  return ARB_OK;
+}
+
+__global__ void route_kernel(const float *__restrict__ scores, int n, float tau, int sense,
+                             uint8_t *__restrict__ escalate) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float s = scores[i];
+  escalate[i] = sense == ARB_ACCEPT_IF_GT ? !(s > tau) : !(s <= tau);
+}
+
+arb_status launch_route(const float *scores, int n, float tau, int sense, uint8_t *escalate, hipStream_t st) {
+  if (n == 0) return ARB_OK;
+  hipLaunchKernelGGL(route_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, scores, n, tau, sense, escalate);
+  ARB_CHECK_LAUNCH("route");
+  return ARB_OK;
+}

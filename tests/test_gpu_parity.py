@@ -1,0 +1,348 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Tolerances: hidden states max|d|/max|ref| <= 2e-2,
+router scores |d| <= 1e-2, decisions identical unless |score - tau| < 1e-2,
+slot indices and untouched cache contents bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from helpers import oracle_model, oracle_params, oracle_pools, rel_err
+from oracle import arb_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+HIDDEN_TOL, SCORE_TOL = 2e-2, 1e-2
+
+
+@pytest.fixture(scope="module")
+def A():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2512_05033_amd as A
+    A.load_library()          # raises if the HIP library is not built: no fallback
+    return A
+
+
+def H():
+    from paper_2512_05033_amd import harness
+    return harness
+
+
+def bf16_np(t):
+    return O.bf16_to_float(W.bf16_bits(t))
+
+
+def rand_bf16(shape, sigma, seed, device="cuda"):
+    return W.normal_bf16(seed, "t", shape, sigma, device)
+
+
+# ------------------------------------------------------------------ input recipes
+
+def test_generator_is_bit_identical_on_cpu_and_gpu(A):
+    a = W.normal_bf16(3, "x", (4096, 130), 0.02, "cpu")
+    b = W.normal_bf16(3, "x", (4096, 130), 0.02, "cuda")
+    assert torch.equal(a, b.cpu())
+    assert torch.equal(W.uniform_ints(3, "i", 10000, 151936, "cpu"), W.uniform_ints(3, "i", 10000, 151936, "cuda").cpu())
+
+
+# ------------------------------------------------------------------- slot mapping
+
+@pytest.mark.parametrize("name", ["C1", "C4", "C5"])
+def test_slot_mapping_bit_exact(A, name):
+    w = W.ALL[name]
+    batch = W.make_batch(w)
+    got = A.arb_slot_mapping(H().device_batch(batch)).cpu().numpy()
+    want = O.slot_mapping(batch.prefix_lens, batch.cu_step_lens, batch.block_tables, w.model.kv_block)
+    assert got.dtype == np.int32 and np.array_equal(got.astype(np.int64), want)
+
+
+# --------------------------------------------------------------------------- GEMM
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (200, 256, 192), (1024, 2048, 1536), (333, 1536, 8960)])
+def test_gemm_store_and_residual(A, M, N, K):
+    a, b = rand_bf16((M, K), 1.0, 11), rand_bf16((N, K), 0.02, 12)
+    ref = bf16_np(a) @ bf16_np(b).T
+    got = A.arb_stage_gemm(a, b, A.ARB_EPI_STORE_BF16)
+    assert rel_err(bf16_np(got), ref) < 4e-3
+    h0 = torch.randn(M, N, device="cuda", dtype=torch.float32)
+    h = h0.clone()
+    A.arb_stage_gemm(a, b, A.ARB_EPI_RESIDUAL_F32, out=h)
+    assert rel_err(h.cpu().numpy(), h0.cpu().numpy().astype(np.float64) + ref) < 1e-5
+
+
+@pytest.mark.parametrize("M,F,K", [(130, 64, 128), (1024, 8960, 1536)])
+def test_gemm_swiglu(A, M, F, K):
+    a, b = rand_bf16((M, K), 1.0, 13), rand_bf16((2 * F, K), 0.05, 14)
+    af, bf = bf16_np(a), bf16_np(b)
+    ref = O.silu(af @ bf[:F].T) * (af @ bf[F:].T)
+    got = A.arb_stage_gemm(a, b, A.ARB_EPI_SWIGLU_BF16)
+    assert got.shape == (M, F) and rel_err(bf16_np(got), ref) < 5e-3
+
+
+def test_gemm_rejects_unsupported_shapes(A):
+    a, b = rand_bf16((8, 96), 1.0, 1), rand_bf16((128, 96), 1.0, 2)
+    with pytest.raises(A.ArbError) as e:
+        A.arb_stage_gemm(a, b)
+    assert e.value.status == A.ARB_EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ per-row stages
+
+def test_rmsnorm_stage(A):
+    x = torch.randn(77, 1536, device="cuda") * 3
+    g = (1 + 0.1 * torch.randn(1536, device="cuda")).contiguous()
+    got = A.arb_stage_rmsnorm(x, g, 1e-6)
+    ref = O.rmsnorm(x.cpu().numpy(), g.cpu().numpy(), 1e-6)
+    assert rel_err(bf16_np(got), ref) < 4e-3
+
+
+def _stage_model(A, shape, seed=5):
+    weights = W.make_weights(W.ModelShape("stage", 1, shape.d_model, shape.n_q_heads, shape.n_kv_heads,
+                                          shape.head_dim, 128, 256), seed, "cuda")
+    m = W.ModelShape("stage", 1, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 128, 256)
+    return m, H().make_model(m, weights)
+
+
+def _ragged_batch(shape, prefix, steps, seed=9):
+    wl = W.Workload("stage", shape, len(prefix), (0, 0), ("fixed", 1, 1), "shuffled", "synthetic", 1.0,
+                    ("const", 0.0), seed)
+    return wl, W.make_batch(wl, prefix_lens=prefix, step_lens=steps)
+
+
+def test_rope_append_stage(A):
+    shape = W.ROUTER_1P5B
+    m, model = _stage_model(A, shape)
+    wl, batch = _ragged_batch(m, [5, 4090, 32767, 16], [7, 3, 1, 16])
+    db = H().device_batch(batch)
+    T = batch.total_tokens
+    qkv = rand_bf16((T, m.qkv_rows), 1.0, 21)
+    ks, vs = W.make_kv_pools(wl, batch, "cuda")
+    k0, v0 = W.bf16_bits(ks[0]).copy(), W.bf16_bits(vs[0]).copy()
+    src = bf16_np(qkv).reshape(T, -1, m.head_dim)
+    A.arb_stage_rope_append(model, qkv, ks[0], vs[0], db)
+    pos = O.positions(batch.prefix_lens, batch.cu_step_lens)
+    Hq, Hkv = m.n_q_heads, m.n_kv_heads
+    q_ref = O.rope(src[:, :Hq], pos, m.rope_base)
+    assert rel_err(bf16_np(qkv).reshape(T, -1, m.head_dim)[:, :Hq], q_ref) < 4e-3
+    assert np.array_equal(W.bf16_bits(qkv).reshape(T, -1, m.head_dim)[:, Hq:],
+                          O.float_to_bf16(src[:, Hq:]))                        # k, v columns of qkv untouched
+    slots = O.slot_mapping(batch.prefix_lens, batch.cu_step_lens, batch.block_tables, 16)
+    kp, vp = k0.copy(), v0.copy()
+    O.kv_append(kp, vp, slots, O.rope(src[:, Hq:Hq + Hkv], pos, m.rope_base), src[:, Hq + Hkv:], 16)
+    k_got, v_got = W.bf16_bits(ks[0]), W.bf16_bits(vs[0])
+    assert np.array_equal(v_got, vp)                                          # values are a pure copy
+    written = np.zeros(kp.shape[0] * 16, bool); written[slots] = True
+    wmask = written.reshape(-1, 16)
+    assert np.array_equal(k_got[~wmask.any(1)], k0[~wmask.any(1)])            # untouched blocks bit-identical
+    flat = lambda a: a.transpose(0, 2, 1, 3).reshape(-1, Hkv, m.head_dim)
+    assert np.array_equal(flat(k_got)[~written], flat(k0)[~written])          # untouched slots bit-identical
+    assert rel_err(O.bf16_to_float(flat(k_got)[written]), O.bf16_to_float(flat(kp)[written])) < 4e-3
+
+
+def test_norm_pool_head_stage_mean_and_last(A):
+    d = 1536
+    _, batch = _ragged_batch(W.ROUTER_1P5B, [0, 0, 0, 0], [1, 64, 17, 128])
+    db = H().device_batch(batch)
+    h = torch.randn(batch.total_tokens, d, device="cuda") * 2
+    g = (1 + 0.1 * torch.randn(d, device="cuda")).contiguous()
+    w = (0.02 * torch.randn(d, device="cuda")).contiguous()
+    y = O.rmsnorm(h.cpu().numpy(), g.cpu().numpy(), 1e-6)
+    for pool, mode in ((A.ARB_POOL_MEAN, "mean"), (A.ARB_POOL_LAST, "last")):
+        ref = O.router_scores(y, batch.cu_step_lens, w.cpu().numpy(), 0.125, mode)
+        tau = float(np.sort(ref)[1] + 0.05)
+        scores, esc, hidden = A.arb_stage_norm_pool_head(h, g, 1e-6, db, w, 0.125, pool, tau)
+        assert np.abs(scores.cpu().numpy() - ref).max() < 1e-4
+        assert np.array_equal(esc.cpu().numpy(), O.route(ref, tau))
+        assert rel_err(bf16_np(hidden), y) < 4e-3
+
+
+# ----------------------------------------------------------------------- decision
+
+def test_route_matches_oracle_including_ties_and_nan(A):
+    s = torch.tensor([0.25, 0.5, 0.75, float("nan"), -float("inf"), float("inf"), 0.5000001], device="cuda")
+    for sense, name in ((A.ARB_ESCALATE_IF_GT, "escalate_if_gt"), (A.ARB_ACCEPT_IF_GT, "accept_if_gt")):
+        assert np.array_equal(A.arb_route(s, 0.5, sense).cpu().numpy(), O.route(s.cpu().numpy(), 0.5, name))
+    big = torch.randn(100003, device="cuda")
+    for tau in (-0.3, 0.0, 1.7):
+        assert np.array_equal(A.arb_route(big, tau).cpu().numpy(), O.route(big.cpu().numpy(), tau))
+    assert A.arb_route(torch.empty(0, device="cuda"), 0.0).numel() == 0
+
+
+# ---------------------------------------------------------------------- attention
+
+def _attention_case(A, shape, prefix, steps, peaky, seed):
+    m, model = _stage_model(A, shape, seed)
+    wl, batch = _ragged_batch(m, prefix, steps, seed)
+    db = H().device_batch(batch)
+    T = batch.total_tokens
+    ks, vs = W.make_kv_pools(wl, batch, "cuda")
+    q = rand_bf16((T, m.qkv_rows), 8.0 if peaky else 1.0, seed + 1)
+    if peaky:
+        # plant a few keys aligned with queries so the running max jumps mid-stream,
+        # one of them in the last, partially filled block of its sequence
+        qf = q.view(T, -1, m.head_dim)
+        for b, (p, s) in enumerate(zip(prefix, steps)):
+            for pos in {0, p // 2, p + s - 1}:
+                blk, off = batch.block_tables[b][pos // 16], pos % 16
+                ks[0][blk, :, off, :] = qf[batch.cu_step_lens[b + 1] - 1, 0, :] * 0.5
+    got = A.arb_stage_attention(model, q, ks[0], vs[0], db)
+    ref = O.append_attention(bf16_np(q).reshape(T, -1, m.head_dim)[:, :m.n_q_heads], W.bf16_bits(ks[0]),
+                             W.bf16_bits(vs[0]), batch.prefix_lens, batch.cu_step_lens, batch.block_tables, 16)
+    return bf16_np(got).reshape(T, m.n_q_heads, m.head_dim), ref
+
+
+@pytest.mark.parametrize("peaky", [False, True])
+@pytest.mark.parametrize("shape,prefix,steps", [
+    (W.ROUTER_1P5B, [300, 77, 1000, 0, 2048], [5, 64, 33, 20, 1]),      # G=6, ragged, empty prefix, decode row
+    (W.TARGET_8B, [4096, 15, 4097], [64, 1, 128]),                       # G=4, 2 query tiles, several splits
+    (W.TINY, [512, 3, 130], [32, 64, 7]),                                # head_dim 64
+])
+def test_attention_stage(A, shape, prefix, steps, peaky):
+    got, ref = _attention_case(A, shape, prefix, steps, peaky, 31)
+    assert rel_err(got, ref) < 1e-2
+    # row-wise as well, so a wrong small row cannot hide behind a large one
+    row_err = np.abs(got - ref).max(axis=-1) / (np.abs(ref).max(axis=-1) + 1e-3)
+    assert row_err.max() < 3e-2
+
+
+# ---------------------------------------------------------------------- end to end
+
+def _oracle_run(sess, pool_mode="mean"):
+    w, batch = sess.workload, sess.batch
+    m, p = oracle_model(w.model), oracle_params(sess.weights)
+    return m, p
+
+
+def _end_to_end(A, w, *, gain_jitter=0.0, sigma=0.02, b_head=0.0, pool_mode="mean"):
+    h = H()
+    pool = A.ARB_POOL_MEAN if pool_mode == "mean" else A.ARB_POOL_LAST
+    batch = W.make_batch(w)
+    # oracle side first, from pristine pools
+    weights_cpu = W.make_weights(w.model, w.seed, "cpu", sigma=sigma, gain_jitter=gain_jitter, b_head=b_head)
+    m, p = oracle_model(w.model), oracle_params(weights_cpu)
+    kp, vp = oracle_pools(*W.make_kv_pools(w, batch, "cpu"))
+    if w.kv_source == "prefill":
+        cu_p = np.concatenate([[0], np.cumsum(batch.prefix_lens)]).astype(np.int32)
+        O.prefill(m, p, kp, vp, W.prompt_token_ids(w, batch), cu_p, batch.block_tables)
+    kp_before = [a.copy() for a in kp]
+    s_ref, e_ref, y_ref = O.score_steps(m, p, kp, vp, batch.token_ids, batch.prefix_lens, batch.cu_step_lens,
+                                        batch.block_tables, batch.tau, pool_mode)
+    sess = h.setup(w, "cuda", gain_jitter=gain_jitter, sigma=sigma, b_head=b_head, pool=pool, batch=batch)
+    scores, esc, hidden = A.arb_score_steps(sess.model, sess.kv, sess.dbatch, batch.tau, want_hidden=True, ws=sess.ws)
+    torch.cuda.synchronize()
+    return sess, (scores, esc, hidden), (s_ref, e_ref, y_ref), (kp, vp, kp_before)
+
+
+def _assert_scores(batch, scores, esc, s_ref, e_ref):
+    s = scores.cpu().numpy()
+    assert np.abs(s - s_ref).max() < SCORE_TOL, np.abs(s - s_ref).max()
+    decided = np.abs(s_ref - batch.tau) >= SCORE_TOL
+    assert np.array_equal(esc.cpu().numpy()[decided], e_ref[decided])
+    assert np.array_equal(esc.cpu().numpy(), O.route(s, batch.tau))      # decision follows the kernel's own score
+
+
+def _assert_cache(sess, kp, vp, kp_before, slots):
+    """Step slots hold the oracle's K/V within bf16 rounding; every other slot is bit-identical."""
+    for l in range(sess.workload.model.n_layers):
+        for got_t, ref in ((sess.kv.k_pools[l], kp[l]), (sess.kv.v_pools[l], vp[l])):
+            got = W.bf16_bits(got_t)
+            flat = lambda a: a.transpose(0, 2, 1, 3).reshape(a.shape[0] * 16, -1)
+            written = np.zeros(got.shape[0] * 16, bool); written[slots] = True
+            g, r = O.bf16_to_float(flat(got)), O.bf16_to_float(flat(ref))
+            assert np.abs(g[written] - r[written]).max() <= 2e-2 * np.abs(r[written]).max()
+            if sess.workload.kv_source == "synthetic":
+                assert np.array_equal(flat(got)[~written], flat(ref)[~written])
+
+
+@pytest.mark.parametrize("pool_mode,gain_jitter", [("mean", 0.0), ("last", 0.1)])
+def test_c1_prefill_then_score(A, pool_mode, gain_jitter):
+    sess, (scores, esc, hidden), (s_ref, e_ref, y_ref), (kp, vp, kp_before) = _end_to_end(
+        A, W.C1, gain_jitter=gain_jitter, b_head=0.01, pool_mode=pool_mode)
+    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+    _assert_scores(sess.batch, scores, esc, s_ref, e_ref)
+    slots = O.slot_mapping(sess.batch.prefix_lens, sess.batch.cu_step_lens, sess.batch.block_tables, 16)
+    _assert_cache(sess, kp, vp, kp_before, slots)
+    # spare blocks were never referenced: still the filler bits
+    spare = sess.batch.spare_blocks
+    fill = W.kv_pool_blocks(W.C1, 0, "k", spare, "cpu")
+    assert torch.equal(sess.kv.k_pools[0][spare].cpu(), fill)
+    # same prefix semantics: scoring again gives the same bits
+    again = A.arb_score_steps(sess.model, sess.kv, sess.dbatch, sess.batch.tau, want_hidden=True, ws=sess.ws)
+    assert torch.equal(again[0], scores) and torch.equal(again[2], hidden)
+
+
+def test_c1_with_large_weights_exercises_attention(A):
+    """sigma 0.08 makes logits O(1..10): attention is far from uniform, so the
+    end-to-end check really depends on the softmax."""
+    sess, (scores, esc, hidden), (s_ref, e_ref, y_ref), _ = _end_to_end(A, W.C1, sigma=0.08, gain_jitter=0.1)
+    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+    _assert_scores(sess.batch, scores, esc, s_ref, e_ref)
+
+
+def test_c2_two_layers_full_batch(A):
+    w = W.scaled(W.C2, n_layers=2)
+    sess, (scores, esc, hidden), (s_ref, e_ref, y_ref), (kp, vp, kp_before) = _end_to_end(A, w, gain_jitter=0.1)
+    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+    _assert_scores(sess.batch, scores, esc, s_ref, e_ref)
+    slots = O.slot_mapping(sess.batch.prefix_lens, sess.batch.cu_step_lens, sess.batch.block_tables, 16)
+    _assert_cache(sess, kp, vp, kp_before, slots)
+
+
+def test_c4_ragged_two_layers_sub_batch(A):
+    """Ragged long-CoT mix on the 1.5B shape: the 6 sequences with the shortest and
+    longest prefixes and steps, 2 layers, against the full pool."""
+    full = W.make_batch(W.C4)
+    pick = sorted({int(np.argmin(full.prefix_lens)), int(np.argmax(full.prefix_lens)),
+                   int(np.argmin(full.step_lens)), int(np.argmax(full.step_lens)), 0, 1})
+    w = W.scaled(W.C4, n_layers=2)
+    batch = full.select(pick)
+    h = H()
+    sess = h.setup(w, "cuda", batch=batch, gain_jitter=0.1)
+    scores, esc, hidden = A.arb_score_steps(sess.model, sess.kv, sess.dbatch, batch.tau, want_hidden=True, ws=sess.ws)
+    m, p = oracle_model(w.model), oracle_params(W.make_weights(w.model, w.seed, "cpu", gain_jitter=0.1))
+    # the oracle gets only the blocks these sequences reference, renumbered densely
+    need = (batch.prefix_lens + batch.step_lens + 15) // 16
+    used = np.concatenate([batch.block_tables[i, :need[i]] for i in range(batch.batch)])
+    remap = -np.ones(batch.n_blocks, np.int64); remap[used] = np.arange(len(used))
+    tables = np.where(np.arange(batch.block_tables.shape[1])[None, :] < need[:, None], remap[batch.block_tables], 0)
+    kp = [W.bf16_bits(W.kv_pool_blocks(w, l, "k", used)).copy() for l in range(2)]
+    vp = [W.bf16_bits(W.kv_pool_blocks(w, l, "v", used)).copy() for l in range(2)]
+    s_ref, e_ref, y_ref = O.score_steps(m, p, kp, vp, batch.token_ids, batch.prefix_lens, batch.cu_step_lens,
+                                        tables, batch.tau)
+    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+    _assert_scores(batch, scores, esc, s_ref, e_ref)
+
+
+def test_target_pass_has_no_head(A):
+    w = W.scaled(W.C3, n_layers=1, batch=2)
+    sess = H().setup(w, "cuda")
+    with pytest.raises(A.ArbError):
+        A.arb_score_steps(sess.model, sess.kv, sess.dbatch, 0.0, scores=torch.zeros(2, device="cuda"))
+    scores, esc, hidden = A.arb_score_steps(sess.model, sess.kv, sess.dbatch, 0.0, want_hidden=True, ws=sess.ws)
+    assert scores is None and esc is None
+    batch = sess.batch
+    m, p = oracle_model(w.model), oracle_params(W.make_weights(w.model, w.seed, "cpu"))
+    kp, vp = oracle_pools(*W.make_kv_pools(w, batch, "cpu"))
+    y_ref = O.forward(m, p, kp, vp, batch.token_ids, batch.prefix_lens, batch.cu_step_lens, batch.block_tables)
+    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+
+
+def test_empty_batch_and_bad_arguments(A):
+    sess = H().setup(W.scaled(W.C1, batch=2), "cuda")
+    empty = A.DeviceBatch(np.zeros(0, np.int32), np.zeros(1, np.int32), np.zeros((0, 0), np.int32),
+                          np.zeros(0, np.int32))
+    s, e, _ = A.arb_score_steps(sess.model, sess.kv, empty, 0.0, ws=sess.ws)
+    assert s.numel() == 0
+    b = sess.batch
+    bad = A.DeviceBatch(b.prefix_lens, np.array([0, 32, 32], np.int32), b.block_tables, b.token_ids[:32])
+    with pytest.raises(A.ArbError) as err:                                   # empty step
+        A.arb_score_steps(sess.model, sess.kv, bad, 0.0, ws=sess.ws)
+    assert err.value.status == A.ARB_EINVAL
+    short = A.DeviceBatch(b.prefix_lens, b.cu_step_lens, b.block_tables[:, :20], b.token_ids)
+    with pytest.raises(A.ArbError) as err:                                   # table too narrow for p+s
+        A.arb_score_steps(sess.model, sess.kv, short, 0.0, ws=sess.ws)
+    assert err.value.status == A.ARB_ECAPACITY
+    with pytest.raises(A.ArbError) as err:                                   # workspace too small
+        A.arb_score_steps(sess.model, sess.kv, sess.dbatch, 0.0, ws=sess.ws[:1024])
+    assert err.value.status == A.ARB_ECAPACITY
