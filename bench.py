@@ -59,7 +59,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2")
-    ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample (0 = skip the CPU baseline)")
+    ap.add_argument("--cpu-layers", type=int, default=-1, help="layers of the oracle sample (-1 = all, 0 = skip the CPU baseline)")
     ap.add_argument("--breakdown", action="store_true", help="also time each stage (extra passes, not in the timed region)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -144,6 +144,8 @@ def main():
                       "gate_up": gu_flops, "down": 2.0 * T * m.d_model * m.d_ffn}
         out["gemm_TFLOPs"] = {k: v / (bd[k] / L * 1e-3) / 1e12 for k, v in gemm_flops.items()}
 
+    if args.cpu_layers < 0:
+        args.cpu_layers = L
     if args.cpu_layers > 0:
         out["cpu_baseline"] = cpu_baseline(w, sess, min(args.cpu_layers, L))
     print(json.dumps(out))

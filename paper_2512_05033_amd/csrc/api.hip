@@ -128,6 +128,7 @@ struct Workspace {
   int32_t *tok_pos, *tok_slot;
   f32x2 *cs;         // [T, hd/2] rotary table
   float *tok_dot;    // [T]
+  float *parts;      // fp32 [8, T, d] split-K partial products of the residual projections
   void *attn_ws;
   size_t attn_ws_bytes, total;
 };
@@ -150,6 +151,7 @@ static Workspace carve(const arb_model_cfg &c, int T, int max_ctx, void *base) {
   w.tok_slot = (int32_t *)take(t * sizeof(int32_t));
   w.cs = (f32x2 *)take(t * (c.head_dim / 2) * sizeof(f32x2));
   w.tok_dot = (float *)take(t * sizeof(float));
+  w.parts = (float *)take(8 * t * c.d_model * sizeof(float));
   w.attn_ws_bytes = attention_ws_bytes(attention_splits_cap(max_ctx), T, c.n_q_heads, c.head_dim);
   w.attn_ws = take(w.attn_ws_bytes);
   w.total = off;
@@ -221,6 +223,10 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
   const int G = c.n_q_heads / c.n_kv_heads;
   const AttnPlan plan = plan_attention(B, bt->prefix_lens_host, bt->cu_step_lens_host, G, c.n_kv_heads);
 
+  // The residual projections (O, down) are split along K when their N is too narrow to fill the
+  // chip; the partial products are added to the residual stream by the norm kernel that follows.
+  const int so = gemm_residual_splits(T, d, c.n_q_heads * c.head_dim), sd = gemm_residual_splits(T, d, c.d_ffn);
+  int pending = 0;
   arb_status s;
   if ((s = launch_token_meta(bt->prefix_lens, bt->cu_step_lens, bt->block_tables, B, T, bt->max_blocks_per_seq,
                              c.kv_block, w.tok_pos, w.tok_slot, st)))
@@ -232,7 +238,8 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
       if (l == 0)
         s = launch_embed_rmsnorm(m->embed, bt->token_ids, m->g_attn[0], c.rms_eps, T, d, w.h, w.x, st);
       else
-        s = launch_rmsnorm(w.h, m->g_attn[l], c.rms_eps, T, d, w.x, st);
+        s = launch_rmsnorm(w.h, w.parts, pending, m->g_attn[l], c.rms_eps, T, d, w.x, st);
+      pending = 0;
     }
     if (s) return s;
     {
@@ -255,10 +262,13 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_OPROJ, st);
-      s = launch_gemm(w.attn, m->wo[l], w.h, T, d, c.n_q_heads * c.head_dim, ARB_EPI_RESIDUAL_F32, st);
+      s = launch_gemm(w.attn, m->wo[l], so > 1 ? w.parts : w.h, T, d, c.n_q_heads * c.head_dim, ARB_EPI_RESIDUAL_F32,
+                      st, so);
+      pending = so > 1 ? so : 0;
     }
     if (s) return s;
-    if ((s = launch_rmsnorm(w.h, m->g_mlp[l], c.rms_eps, T, d, w.x, st))) return s;
+    if ((s = launch_rmsnorm(w.h, w.parts, pending, m->g_mlp[l], c.rms_eps, T, d, w.x, st))) return s;
+    pending = 0;
     {
       TraceScope t(m, ARB_STAGE_GATE_UP, st);
       s = launch_gemm(w.x, m->wgu[l], w.act, T, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, st);
@@ -266,11 +276,12 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_DOWN, st);
-      s = launch_gemm(w.act, m->wd[l], w.h, T, d, c.d_ffn, ARB_EPI_RESIDUAL_F32, st);
+      s = launch_gemm(w.act, m->wd[l], sd > 1 ? w.parts : w.h, T, d, c.d_ffn, ARB_EPI_RESIDUAL_F32, st, sd);
+      pending = sd > 1 ? sd : 0;
     }
     if (s) return s;
   }
-  if ((s = launch_final_norm_head(w.h, m->g_final, c.rms_eps, T, d, with_head ? m->w_head : nullptr,
+  if ((s = launch_final_norm_head(w.h, w.parts, pending, m->g_final, c.rms_eps, T, d, with_head ? m->w_head : nullptr,
                                   (bf16 *)hidden_out, with_head ? w.tok_dot : nullptr, st)))
     return s;
   if (with_head)
@@ -344,7 +355,7 @@ extern "C" arb_status arb_stage_rmsnorm(const float *x, const float *g, float ep
   if (T < 0) return arb_fail(ARB_EINVAL, "arb_stage_rmsnorm: T = %d", T);
   if (T == 0) return ARB_OK;
   if (!x || !g || !out) return arb_fail(ARB_EINVAL, "arb_stage_rmsnorm: null pointer");
-  return launch_rmsnorm(x, g, eps, T, d, (bf16 *)out, (hipStream_t)stream);
+  return launch_rmsnorm(const_cast<float *>(x), nullptr, 0, g, eps, T, d, (bf16 *)out, (hipStream_t)stream);
 }
 
 extern "C" arb_status arb_stage_rope_append(const arb_model *m, void *qkv, void *k_pool, void *v_pool,
@@ -383,7 +394,7 @@ extern "C" arb_status arb_stage_norm_pool_head(const float *h, const float *g_fi
   const size_t need = (size_t)batch->total_tokens * sizeof(float);
   if (!ws || ws_bytes < need) return arb_fail(ARB_ECAPACITY, "arb_stage_norm_pool_head: workspace %zu < %zu bytes", ws_bytes, need);
   hipStream_t st = (hipStream_t)stream;
-  if (arb_status s = launch_final_norm_head(h, g_final, eps, batch->total_tokens, d, w_head, (bf16 *)hidden_out,
+  if (arb_status s = launch_final_norm_head(h, nullptr, 0, g_final, eps, batch->total_tokens, d, w_head, (bf16 *)hidden_out,
                                             (float *)ws, st))
     return s;
   return launch_pool_route((const float *)ws, batch->cu_step_lens, batch->batch, b_head, pool, tau, scores, escalate, st);

@@ -41,7 +41,11 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
 
 // gemm.hip
-arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st);
+// With splits > 1 (residual epilogue only) C is not accumulated into: split s writes its fp32 partial
+// product to C + s*M*N and the consumer adds the partials to the residual stream (see the norm kernels).
+arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st,
+                       int splits = 1);
+int gemm_residual_splits(int M, int N, int K);
 
 // attention.hip
 struct AttnPlan {
@@ -65,11 +69,13 @@ arb_status launch_rope_table(const int32_t *tok_pos, int total_tokens, int head_
                              hipStream_t st);
 arb_status launch_embed_rmsnorm(const bf16 *embed, const int32_t *token_ids, const float *g, float eps, int T, int d,
                                 float *h, bf16 *x, hipStream_t st);
-arb_status launch_rmsnorm(const float *h, const float *g, float eps, int T, int d, bf16 *x, hipStream_t st);
+// parts/n_parts: fp32 partial products [n_parts, T, d] that are first added to h (and h is updated).
+arb_status launch_rmsnorm(float *h, const float *parts, int n_parts, const float *g, float eps, int T, int d, bf16 *x,
+                          hipStream_t st);
 arb_status launch_rope_append(bf16 *qkv, const f32x2 *cs, const int32_t *tok_slot, bf16 *k_pool, bf16 *v_pool, int T,
                               int n_q_heads, int n_kv_heads, int head_dim, hipStream_t st);
-arb_status launch_final_norm_head(const float *h, const float *g, float eps, int T, int d, const float *w_head,
-                                  bf16 *hidden_out, float *tok_dot, hipStream_t st);
+arb_status launch_final_norm_head(const float *h, const float *parts, int n_parts, const float *g, float eps, int T,
+                                  int d, const float *w_head, bf16 *hidden_out, float *tok_dot, hipStream_t st);
 arb_status launch_pool_route(const float *tok_dot, const int32_t *cu_step_lens, int batch, float b_head, int pool,
                              float tau, float *scores, uint8_t *escalate, hipStream_t st);
 arb_status launch_route(const float *scores, int n, float tau, int sense, uint8_t *escalate, hipStream_t st);

@@ -84,11 +84,16 @@ arb_status launch_rope_table(const int32_t *tok_pos, int total_tokens, int head_
 // sum-of-squares pass and the scaling pass (d <= 256*8*ROW_VECS).
 #define ROW_VECS 4
 
+// With n_parts > 0 the row is first completed by the split-K partial products of
+// the preceding residual projection: h = h_in + sum_s parts[s] (fixed order), and
+// written back through h_out when that is not null.
 template <bool EMBED, bool HEAD>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h_in, const bf16 *__restrict__ embed,
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h_in, const float *__restrict__ parts,
+                                                      int n_parts, size_t part_stride,
+                                                      const bf16 *__restrict__ embed,
                                                       const int32_t *__restrict__ token_ids,
                                                       const float *__restrict__ g, float eps, int d,
-                                                      float *__restrict__ h_out, bf16 *__restrict__ x_out,
+                                                      float *h_out, bf16 *__restrict__ x_out,
                                                       const float *__restrict__ w_head, float *__restrict__ tok_dot) {
   __shared__ float red[4];
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -107,7 +112,19 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
         *(f32x4 *)(dst + 4) = f32x4{v[it][4], v[it][5], v[it][6], v[it][7]};
       } else {
         const float *src = h_in + (size_t)row * d + c;
-        const f32x4 a = *(const f32x4 *)src, b = *(const f32x4 *)(src + 4);
+        f32x4 a = *(const f32x4 *)src, b = *(const f32x4 *)(src + 4);
+        if (n_parts > 0) {
+          for (int sp = 0; sp < n_parts; ++sp) {
+            const float *ps = parts + sp * part_stride + (size_t)row * d + c;
+            a += *(const f32x4 *)ps;
+            b += *(const f32x4 *)(ps + 4);
+          }
+          if (h_out) {                          // the last norm of a pass has no later reader of h
+            float *dst = h_out + (size_t)row * d + c;
+            *(f32x4 *)dst = a;
+            *(f32x4 *)(dst + 4) = b;
+          }
+        }
         v[it][0] = a[0]; v[it][1] = a[1]; v[it][2] = a[2]; v[it][3] = a[3];
         v[it][4] = b[0]; v[it][5] = b[1]; v[it][6] = b[2]; v[it][7] = b[3];
       }
@@ -155,28 +172,32 @@ arb_status launch_embed_rmsnorm(const bf16 *embed, const int32_t *token_ids, con
                                 float *h, bf16 *x, hipStream_t st) {
   if (T == 0) return ARB_OK;
   if (arb_status s = check_row_width(d)) return s;
-  hipLaunchKernelGGL((rmsnorm_kernel<true, false>), dim3(T), dim3(256), 0, st, (const float *)nullptr, embed,
-                     token_ids, g, eps, d, h, x, (const float *)nullptr, (float *)nullptr);
+  hipLaunchKernelGGL((rmsnorm_kernel<true, false>), dim3(T), dim3(256), 0, st, (const float *)nullptr,
+                     (const float *)nullptr, 0, (size_t)0, embed, token_ids, g, eps, d, h, x, (const float *)nullptr,
+                     (float *)nullptr);
   ARB_CHECK_LAUNCH("embed_rmsnorm");
   return ARB_OK;
 }
 
-arb_status launch_rmsnorm(const float *h, const float *g, float eps, int T, int d, bf16 *x, hipStream_t st) {
+arb_status launch_rmsnorm(float *h, const float *parts, int n_parts, const float *g, float eps, int T, int d, bf16 *x,
+                          hipStream_t st) {
   if (T == 0) return ARB_OK;
   if (arb_status s = check_row_width(d)) return s;
-  hipLaunchKernelGGL((rmsnorm_kernel<false, false>), dim3(T), dim3(256), 0, st, h, (const bf16 *)nullptr,
-                     (const int32_t *)nullptr, g, eps, d, (float *)nullptr, x, (const float *)nullptr,
-                     (float *)nullptr);
+  hipLaunchKernelGGL((rmsnorm_kernel<false, false>), dim3(T), dim3(256), 0, st, (const float *)h, parts, n_parts,
+                     (size_t)T * d, (const bf16 *)nullptr, (const int32_t *)nullptr, g, eps, d, h, x,
+                     (const float *)nullptr, (float *)nullptr);
   ARB_CHECK_LAUNCH("rmsnorm");
   return ARB_OK;
 }
 
-arb_status launch_final_norm_head(const float *h, const float *g, float eps, int T, int d, const float *w_head,
-                                  bf16 *hidden_out, float *tok_dot, hipStream_t st) {
+arb_status launch_final_norm_head(const float *h, const float *parts, int n_parts, const float *g, float eps, int T,
+                                  int d, const float *w_head, bf16 *hidden_out, float *tok_dot, hipStream_t st) {
   if (T == 0) return ARB_OK;
   if (arb_status s = check_row_width(d)) return s;
-  hipLaunchKernelGGL((rmsnorm_kernel<false, true>), dim3(T), dim3(256), 0, st, h, (const bf16 *)nullptr,
-                     (const int32_t *)nullptr, g, eps, d, (float *)nullptr, hidden_out, w_head, tok_dot);
+  // the residual stream is not needed after the last norm, so the completed row is not written back
+  hipLaunchKernelGGL((rmsnorm_kernel<false, true>), dim3(T), dim3(256), 0, st, h, parts, n_parts, (size_t)T * d,
+                     (const bf16 *)nullptr, (const int32_t *)nullptr, g, eps, d, (float *)nullptr, hidden_out, w_head,
+                     tok_dot);
   ARB_CHECK_LAUNCH("final_norm_head");
   return ARB_OK;
 }

@@ -34,6 +34,9 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {   // element offset
   return row * BK + ((chunk ^ (row & 7)) << 3);
 }
 
+// Internal epilogue: split s of a split-K launch stores its fp32 partial product to C + s*M*N.
+constexpr int EPI_PARTIAL_F32 = 3;
+
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                    void *__restrict__ Cv, int M, int N, int K, int tiles_m,
@@ -76,6 +79,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16 *__restrict__ A, c
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // K range of this workgroup (the whole of K unless the launch is split along K)
+  const int nk_all = K / BK;
+  const int kt_begin = (int)((long long)nk_all * blockIdx.y / gridDim.y);
+  const int nk = (int)((long long)nk_all * (blockIdx.y + 1) / gridDim.y) - kt_begin;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a_src[i] += (size_t)kt_begin * BK;
+    b_src[i] += (size_t)kt_begin * BK;
+  }
+
   u32x4 ra[4], rb[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -89,7 +102,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16 *__restrict__ A, c
   }
   __syncthreads();
 
-  const int nk = K / BK;
   const int frag_row = lane & 31, frag_half = lane >> 5;
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
@@ -150,6 +162,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16 *__restrict__ A, c
           if (m < M) {
             if (EPI == ARB_EPI_STORE_BF16) {
               ((bf16 *)Cv)[(size_t)m * N + col] = (bf16)acc[i][j][r];
+            } else if (EPI == EPI_PARTIAL_F32) {
+              ((float *)Cv)[((size_t)blockIdx.y * M + m) * N + col] = acc[i][j][r];
             } else {
               float *dst = (float *)Cv + (size_t)m * N + col;
               *dst += acc[i][j][r];
@@ -162,7 +176,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16 *__restrict__ A, c
 
 }  // namespace
 
-arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st) {
+int gemm_residual_splits(int M, int N, int K) {
+  // enough workgroups to fill 256 CUs, each keeping at least 4 K-steps; the partials cost
+  // 8 bytes of traffic per element and split, so no more splits than that needs
+  const int tiles = ceil_div(M, BM) * (N / BN), nk = K / BK;
+  int s = ceil_div(384, tiles);
+  if (s > nk / 4) s = nk / 4;
+  if (s > 8) s = 8;
+  return s < 1 ? 1 : s;
+}
+
+arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st,
+                       int splits) {
   if (M == 0) return ARB_OK;
   if (M < 0 || N <= 0 || K <= 0) return arb_fail(ARB_EINVAL, "gemm: M=%d N=%d K=%d", M, N, K);
   if (K % BK != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm: K=%d is not a multiple of %d", K, BK);
@@ -175,13 +200,18 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
     if (N % BN != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm: N=%d is not a multiple of %d", N, BN);
     tiles_n = N / BN;
   }
-  const dim3 grid(tiles_m * tiles_n), block(256);
+  if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32) return arb_fail(ARB_EINVAL, "gemm: split-K needs the residual epilogue");
+  if (splits < 1 || splits > K / BK) return arb_fail(ARB_EINVAL, "gemm: %d splits of %d K-steps", splits, K / BK);
+  const dim3 grid(tiles_m * tiles_n, splits), block(256);
   switch (epilogue) {
     case ARB_EPI_STORE_BF16:
       hipLaunchKernelGGL((gemm_kernel<ARB_EPI_STORE_BF16>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
       break;
     case ARB_EPI_RESIDUAL_F32:
-      hipLaunchKernelGGL((gemm_kernel<ARB_EPI_RESIDUAL_F32>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
+      if (splits > 1)
+        hipLaunchKernelGGL((gemm_kernel<EPI_PARTIAL_F32>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
+      else
+        hipLaunchKernelGGL((gemm_kernel<ARB_EPI_RESIDUAL_F32>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
       break;
     case ARB_EPI_SWIGLU_BF16:
       hipLaunchKernelGGL((gemm_kernel<ARB_EPI_SWIGLU_BF16>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
