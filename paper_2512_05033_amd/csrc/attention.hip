@@ -8,15 +8,18 @@
 // streamed from HBM once per 128 rows that need it; rows of different query
 // tiles of the same (b, hk) meet in L2.
 //
-// Per 64-key tile: K goes to LDS row-major [key][hd] (XOR-swizzled 16-byte
-// chunks), V goes to LDS transposed [hd][key] so that both MFMA operands are
-// contiguous reads.  S^T = K Q^T (keys are MFMA rows, queries are columns), so a
+// Per 64-key tile, K and V go to LDS row-major [key][hd] with XOR-swizzled
+// 16-byte chunks.  S^T = K Q^T (keys are MFMA rows, queries are columns), so a
 // lane owns one query column: the row max / row sum are in-lane reductions plus
 // one cross-half shuffle, and exp2(S^T - m) is already laid out as the B operand
-// of O^T = V^T P^T.  The pairing of MFMA contraction slots with keys follows the
-// 32x32 D layout (lane half h, registers 8u..8u+7 of tile t hold keys
-// 32t+16u+4h+{0..3} and 32t+16u+8+4h+{0..3}); V^T fragments are read with the
-// same pairing.
+// of O^T = V^T P^T.  The V^T fragments (a lane needs 8 keys of one hd column) come
+// from the LDS transpose read ds_read_b64_tr_b16: within 16 lanes, source lane j
+// points at 4 consecutive columns of one row and lane i receives element i%4 of
+// source lanes i/4, 4+i/4, 8+i/4, 12+i/4; with source lane j addressing key j/4,
+// columns 4*(j%4).., lane i gets column i of four consecutive keys.  The pairing of
+// MFMA contraction slots with keys follows the 32x32 D layout (lane half h,
+// registers 8u..8u+7 of tile t hold keys 32t+16u+4h+{0..3} and
+// 32t+16u+8+4h+{0..3}); V^T is read with the same pairing.
 #include "common.h"
 
 #include <math.h>
@@ -25,21 +28,96 @@ namespace {
 
 constexpr int QROWS = 128;     // query rows per workgroup
 constexpr int KT = 64;         // keys per tile
-constexpr int VT_STRIDE = KT + 4;   // elements; keeps 8-byte alignment and spreads banks
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 template <int HD>
 struct Smem {
   __attribute__((aligned(16))) bf16 k[KT * HD];
-  __attribute__((aligned(16))) bf16 vt[HD * VT_STRIDE];
+  __attribute__((aligned(16))) bf16 v[KT * HD];
 };
 
 template <int HD>
-__device__ __forceinline__ int k_off(int key, int chunk) {   // 16-byte chunk within a key row
+__device__ __forceinline__ int kv_off(int key, int chunk) {   // element offset of a 16-byte chunk of a key row
   return key * HD + ((chunk ^ (key & 7)) << 3);
 }
 
+// One 64-key tile for one wave: scores, online softmax update, O^T accumulation.
+template <int HD>
+__device__ __forceinline__ void attend_tile(const Smem<HD> &sm, const bf16x8 (&qf)[HD / 16], f32x16 (&o)[HD / 32],
+                                            float &m_run, float &l_run, int ts, int limit, float scale_log2, int col,
+                                            int half, int lane) {
+  constexpr int KSTEPS = HD / 16, MT = HD / 32;
+  f32x16 st[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      const bf16x8 kf = *(const bf16x8 *)&sm.k[kv_off<HD>(t * 32 + col, kk * 2 + half)];
+      st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
+    }
+  }
+  // running max over the raw logits (the positive scale commutes with max)
+  float mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      // causal limit of this lane's query row (also hides keys past the context)
+      const int j = ts + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      st[t][r] = j <= limit ? st[t][r] : -INFINITY;
+      mx = fmaxf(mx, st[t][r]);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(m_run, mx * scale_log2);
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;
+  if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {     // some row's max moved: rescale the state
+    const float alpha = exp2f(m_run - m_use);                // m_run = -inf -> 0
+    l_run *= alpha;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[mt][r] *= alpha;
+    m_run = m_new;
+  }
+  float l_add = 0.f;
+  bf16x8 pf[2][2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pv = exp2f(fmaf(st[t][r], scale_log2, -m_use));
+      l_add += pv;
+      pf[t][r >> 3][r & 7] = (bf16)pv;
+    }
+  l_run += l_add;
+  // O^T += V^T P^T; V^T fragments by transpose reads (see the header comment)
+  const int j16 = lane & 15;
+  const int vcol = 16 * ((lane >> 4) & 1) + 4 * (j16 & 3);     // within a 32-column tile
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int key0 = t * 32 + u * 16 + 4 * half + (j16 >> 2);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int c = mt * 32 + vcol;
+        const bf16 *a0 = &sm.v[kv_off<HD>(key0, c >> 3) + (c & 7)];
+        const bf16 *a1 = &sm.v[kv_off<HD>(key0 + 8, c >> 3) + (c & 7)];
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a0);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a1);
+        union { s16x4 s[2]; bf16x8 b; } vf;
+        vf.s[0] = lo;
+        vf.s[1] = hi;
+        o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, pf[t][u], o[mt], 0, 0, 0);
+      }
+    }
+}
+
 template <int HD, bool SPLIT>
-__global__ __launch_bounds__(256) void attention_kernel(
+__global__ __launch_bounds__(256, 2) void attention_kernel(
     const bf16 *__restrict__ q, int q_row_stride, const bf16 *__restrict__ k_pool, const bf16 *__restrict__ v_pool,
     const int32_t *__restrict__ block_tables, int max_blocks, const int32_t *__restrict__ prefix_lens,
     const int32_t *__restrict__ cu, int T, int Hq, int Hkv, int max_qtiles, int kv_chunk, float scale_log2,
@@ -66,6 +144,7 @@ __global__ __launch_bounds__(256) void attention_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
+  const bool wave_active = row0 + wave * 32 < rows;    // waves past the last row only help with the loads
 
   // this lane's query row
   const int row = row0 + wave * 32 + col;
@@ -98,6 +177,8 @@ __global__ __launch_bounds__(256) void attention_kernel(
   const int32_t *table = block_tables + (size_t)b * max_blocks;
   u32x4 rk[LOADS], rv[LOADS];
 
+  // Keys past the context are never visible, but their V rows are zeroed so that a
+  // zero probability cannot meet a non-finite stale value.
   auto load_tile = [&](int tile_start) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
@@ -117,10 +198,8 @@ __global__ __launch_bounds__(256) void attention_kernel(
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int c = tid + 256 * i, key = c / CPK, chunk = c - key * CPK;
-      *(u32x4 *)&sm.k[k_off<HD>(key, chunk)] = rk[i];
-      const bf16 *ve = (const bf16 *)&rv[i];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) sm.vt[(chunk * 8 + e) * VT_STRIDE + key] = ve[e];
+      *(u32x4 *)&sm.k[kv_off<HD>(key, chunk)] = rk[i];
+      *(u32x4 *)&sm.v[kv_off<HD>(key, chunk)] = rv[i];
     }
   };
 
@@ -130,63 +209,7 @@ __global__ __launch_bounds__(256) void attention_kernel(
     store_tile();
     __syncthreads();
     if (ts + KT < kv_end) load_tile(ts + KT);
-
-    // S^T tile: 64 keys x 32 queries per wave
-    f32x16 st[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < KSTEPS; ++kk) {
-        const bf16x8 kf = *(const bf16x8 *)&sm.k[k_off<HD>(t * 32 + col, kk * 2 + half)];
-        st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
-      }
-    }
-    // scale, mask, running max
-    float m_new = m_run;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = ts + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float v = j <= limit ? st[t][r] * scale_log2 : -INFINITY;
-        st[t][r] = v;
-        m_new = fmaxf(m_new, v);
-      }
-    m_new = fmaxf(m_new, __shfl_xor(m_new, 32, 64));
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = exp2f(m_run - m_use);          // m_run = -inf -> 0
-    m_run = m_new;
-    float l_add = 0.f;
-    bf16x8 pf[2][2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pv = exp2f(st[t][r] - m_use);
-        l_add += pv;
-        pf[t][r >> 3][r & 7] = (bf16)pv;
-      }
-    l_run = l_run * alpha + l_add;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[mt][r] *= alpha;
-    // O^T += V^T P^T
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int kbase = t * 32 + u * 16 + 4 * half;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const bf16 *vrow = &sm.vt[(mt * 32 + col) * VT_STRIDE + kbase];
-          const bf16x4 lo = *(const bf16x4 *)vrow, hi = *(const bf16x4 *)(vrow + 8);
-          const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          o[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][u], o[mt], 0, 0, 0);
-        }
-      }
+    if (wave_active) attend_tile<HD>(sm, qf, o, m_run, l_run, ts, limit, scale_log2, col, half, lane);
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -254,7 +277,7 @@ __global__ __launch_bounds__(64) void attention_merge_kernel(const float *__rest
 
 }  // namespace
 
-static const int kTargetWorkgroups = 1024;   // ~4 per CU on 256 CUs
+static const int kTargetWorkgroups = 512;    // two resident workgroups per CU on 256 CUs
 static const int kMinChunk = 256, kMaxSplits = 64;
 
 int attention_splits_cap(int max_ctx) {
