@@ -257,7 +257,7 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
       TraceScope t(m, ARB_STAGE_ATTENTION, st);
       s = launch_attention(w.qkv, m->qkv_rows(), (const bf16 *)kv->k_pool[l], (const bf16 *)kv->v_pool[l],
                            bt->block_tables, bt->max_blocks_per_seq, bt->prefix_lens, bt->cu_step_lens, B, T,
-                           c.n_q_heads, c.n_kv_heads, c.head_dim, plan, w.attn, w.attn_ws, w.attn_ws_bytes, st);
+                           c.n_q_heads, c.n_kv_heads, c.head_dim, plan, w.tok_pos, w.attn, w.attn_ws, w.attn_ws_bytes, st);
     }
     if (s) return s;
     {
@@ -346,7 +346,7 @@ extern "C" arb_status arb_stage_attention(const arb_model *m, const void *q, int
                                        c.n_q_heads / c.n_kv_heads, c.n_kv_heads);
   return launch_attention((const bf16 *)q, q_row_stride, (const bf16 *)k_pool, (const bf16 *)v_pool,
                           batch->block_tables, batch->max_blocks_per_seq, batch->prefix_lens, batch->cu_step_lens,
-                          batch->batch, batch->total_tokens, c.n_q_heads, c.n_kv_heads, c.head_dim, plan, (bf16 *)out,
+                          batch->batch, batch->total_tokens, c.n_q_heads, c.n_kv_heads, c.head_dim, plan, nullptr, (bf16 *)out,
                           ws, ws_bytes, (hipStream_t)stream);
 }
 

@@ -39,7 +39,9 @@ struct Smem {
 
 template <int HD>
 __device__ __forceinline__ int kv_off(int key, int chunk) {   // element offset of a 16-byte chunk of a key row
-  return key * HD + ((chunk ^ (key & 7)) << 3);
+  // 16 lanes (256 bytes = all banks) are served together: with 256-byte rows the 16 keys need 16
+  // distinct chunk slots, with 128-byte rows 8 slots times the row parity
+  return key * HD + ((chunk ^ (HD == 128 ? (key & 15) : ((key >> 1) & 7))) << 3);
 }
 
 // One 64-key tile for one wave: scores, online softmax update, O^T accumulation.
@@ -315,12 +317,13 @@ size_t attention_ws_bytes(int max_splits_cap, int total_tokens, int n_q_heads, i
 arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool, const bf16 *v_pool,
                             const int32_t *block_tables, int max_blocks_per_seq, const int32_t *prefix_lens,
                             const int32_t *cu_step_lens, int batch, int total_tokens, int n_q_heads, int n_kv_heads,
-                            int head_dim, const AttnPlan &plan, bf16 *out, void *ws, size_t ws_bytes, hipStream_t st) {
+                            int head_dim, const AttnPlan &plan, const int32_t *tok_pos_in, bf16 *out, void *ws, size_t ws_bytes,
+                            hipStream_t st) {
   if (batch == 0 || total_tokens == 0) return ARB_OK;
   if (head_dim != 64 && head_dim != 128) return arb_fail(ARB_EUNSUPPORTED, "attention: head_dim %d", head_dim);
   const bool split = plan.max_splits > 1;
   float *part_acc = nullptr, *part_ml = nullptr;
-  int32_t *tok_pos = nullptr;
+  const int32_t *tok_pos = tok_pos_in;      // position of every step token; computed here when not given
   if (split) {
     const size_t need = attention_ws_bytes(plan.max_splits, total_tokens, n_q_heads, head_dim);
     if (ws == nullptr || ws_bytes < need)
@@ -329,10 +332,12 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
     char *pws = (char *)ws;
     part_acc = (float *)pws; pws += align_up(rows * head_dim * sizeof(float), 256);
     part_ml = (float *)pws;  pws += align_up(rows * 2 * sizeof(float), 256);
-    tok_pos = (int32_t *)pws;
-    if (arb_status s = launch_token_meta(prefix_lens, cu_step_lens, block_tables, batch, total_tokens,
-                                         max_blocks_per_seq, ARB_KV_BLOCK, tok_pos, nullptr, st))
-      return s;
+    if (!tok_pos) {
+      tok_pos = (int32_t *)pws;
+      if (arb_status s = launch_token_meta(prefix_lens, cu_step_lens, block_tables, batch, total_tokens,
+                                           max_blocks_per_seq, ARB_KV_BLOCK, (int32_t *)pws, nullptr, st))
+        return s;
+    }
   }
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)head_dim));
   const dim3 grid(plan.max_splits, n_kv_heads * plan.max_qtiles, batch), block(256);

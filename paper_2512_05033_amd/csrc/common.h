@@ -59,7 +59,8 @@ int attention_splits_cap(int max_ctx);   // largest max_splits plan_attention ca
 arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool, const bf16 *v_pool,
                             const int32_t *block_tables, int max_blocks_per_seq, const int32_t *prefix_lens,
                             const int32_t *cu_step_lens, int batch, int total_tokens, int n_q_heads, int n_kv_heads,
-                            int head_dim, const AttnPlan &plan, bf16 *out, void *ws, size_t ws_bytes, hipStream_t st);
+                            int head_dim, const AttnPlan &plan, const int32_t *tok_pos_in, bf16 *out, void *ws, size_t ws_bytes,
+                            hipStream_t st);
 
 // elementwise.hip
 arb_status launch_token_meta(const int32_t *prefix_lens, const int32_t *cu_step_lens, const int32_t *block_tables,
