@@ -4,9 +4,8 @@
 // Both operands are K-contiguous, so a lane's MFMA fragment (8 consecutive k of
 // one row) is one 16-byte LDS read.  A workgroup of 4 waves owns a 128x128 tile
 // of C; each wave owns 64x64 of it as 2x2 MFMA tiles.  K is walked in steps of
-// 64 through a double-buffered LDS stage fed from registers, with the global
-// loads running two steps ahead of the MFMAs (HBM/L2 latency is several times
-// one step's MFMA time).  16-byte LDS chunks are XOR-swizzled by row/2: a 16-byte
+// 64 through a double-buffered LDS stage filled by direct-to-LDS global loads
+// (global_load_lds_dwordx4), one step ahead of the MFMAs.  16-byte LDS chunks are XOR-swizzled by row/2: a 16-byte
 // LDS read is served 16 lanes (256 bytes, all 64 banks) at a time, rows are 128
 // bytes, so 16 consecutive rows must spread over (row parity, 8 chunk slots).
 //
@@ -19,6 +18,9 @@ namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int LDS_TILE = BM * BK;   // elements per operand tile
+
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give
 // every XCD a contiguous range of logical tiles so that the m-tiles that share a
@@ -42,8 +44,9 @@ template <int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                    void *__restrict__ Cv, int M, int N, int K, int tiles_m,
                                                    int tiles_n) {
-  __shared__ __attribute__((aligned(16))) bf16 As[2][LDS_TILE];
-  __shared__ __attribute__((aligned(16))) bf16 Bs[2][LDS_TILE];
+  // One array per operand and stage: the compiler orders LDS reads against in-flight direct-to-LDS
+  // loads by object, so separate objects let the reads of one stage overlap the loads into the other.
+  __shared__ __attribute__((aligned(16))) bf16 As0[LDS_TILE], As1[LDS_TILE], Bs0[LDS_TILE], Bs1[LDS_TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -51,12 +54,14 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
   const int tile_n = logical / tiles_m, tile_m = logical - tile_n * tiles_m;
   const int m0 = tile_m * BM;
 
-  // global source rows of this thread's four 16-byte chunks per operand
+  // Global source of this thread's four 16-byte chunks per operand.  Tiles are brought in by
+  // direct-to-LDS loads: one wave-wide load fills 1 KB of LDS in lane order (8 tile rows of 8
+  // chunk slots), so the XOR swizzle is applied on the global side: the lane that owns slot
+  // (row, p) fetches logical chunk p ^ swz(row).
   const bf16 *a_src[4], *b_src[4];
-  int st_off[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int c = tid + 256 * i, row = c >> 3, chunk = c & 7;
+    const int c = tid + 256 * i, row = c >> 3, chunk = (c & 7) ^ ((row >> 1) & 7);
     int am = m0 + row;
     am = am < M ? am : M - 1;                       // tail rows re-read the last row; never stored
     a_src[i] = A + (size_t)am * K + chunk * 8;
@@ -69,7 +74,6 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
       bn = tile_n * BN + row;
     }
     b_src[i] = B + (size_t)bn * K + chunk * 8;
-    st_off[i] = lds_off(row, chunk);
   }
 
   f32x16 acc[2][2];
@@ -90,23 +94,17 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
     b_src[i] += (size_t)kt_begin * BK;
   }
 
-  // Software pipeline, two K-steps deep: while step kt is multiplied out of LDS buffer kt%2, the
-  // global loads of step kt+2 are in flight into one register set and the loads of step kt+1
-  // (issued one step earlier, into the other set) are written to the other LDS buffer.
-  u32x4 ra[2][4], rb[2][4];
+  // While step kt is multiplied out of LDS buffer kt%2, the loads of step kt+1 stream from global
+  // memory straight into the other buffer (no register staging, no LDS-write phase); the barrier
+  // that ends the step also waits for them.
   const int frag_row = lane & 31, frag_half = lane >> 5;
-  auto gload = [&](int set, int kt) {
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma = [&](int buf, int kt) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      ra[set][i] = *(const u32x4 *)(a_src[i] + (size_t)kt * BK);
-      rb[set][i] = *(const u32x4 *)(b_src[i] + (size_t)kt * BK);
-    }
-  };
-  auto lstore = [&](int buf, int set) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *(u32x4 *)&As[buf][st_off[i]] = ra[set][i];
-      *(u32x4 *)&Bs[buf][st_off[i]] = rb[set][i];
+      const int slot = (i * 4 + wave_u) * 512;      // 1 KB (8 rows) per wave-wide load
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * BK), LDS_PTR((buf ? As1 : As0) + slot), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src[i] + (size_t)kt * BK), LDS_PTR((buf ? Bs1 : Bs0) + slot), 16, 0, 0);
     }
   };
   // MFMAs of one K-step; the LDS reads of sub-step kk+1 are issued before the MFMAs of kk.
@@ -115,8 +113,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
     auto frags = [&](int slot, int kk) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        fa[slot][i] = *(const bf16x8 *)&As[buf][lds_off(wm * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
-        fb[slot][i] = *(const bf16x8 *)&Bs[buf][lds_off(wn * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
+        fa[slot][i] = *(const bf16x8 *)&(buf ? As1 : As0)[lds_off(wm * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
+        fb[slot][i] = *(const bf16x8 *)&(buf ? Bs1 : Bs0)[lds_off(wn * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
       }
     };
     frags(0, 0);
@@ -132,25 +130,20 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
     }
   };
 
-  // The loop body is kept free of branches (loads past the end are clamped to the last step and
-  // their LDS copy is never read): the compiler's wait-count tracking is exact only in
-  // straight-line code, and a conservative wait here would drain the loads just issued.
+  // The loop body is branch-free (loads past the end are clamped to the last step; their copy is
+  // never read).
   const int last = nk - 1;
-  gload(0, 0);
-  gload(1, min(1, last));
-  lstore(0, 0);
+  dma(0, 0);
   __syncthreads();
   int kt = 0;
   for (; kt + 2 <= nk; kt += 2) {
-    gload(0, min(kt + 2, last));
+    dma(1, kt + 1);
     __builtin_amdgcn_sched_barrier(0);      // keep the loads ahead of the MFMAs they overlap with
     compute(0);
-    lstore(1, 1);
     __syncthreads();
-    gload(1, min(kt + 3, last));
+    dma(0, min(kt + 2, last));
     __builtin_amdgcn_sched_barrier(0);
     compute(1);
-    lstore(0, 0);
     __syncthreads();
   }
   if (kt < nk) compute(0);     // odd number of steps: the last one sits in buffer 0
@@ -206,8 +199,7 @@ template <int EPI>
 __global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                          void *__restrict__ Cv, int M, int N, int K, int tiles_m,
                                                          int tiles_n) {
-  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  bf16 *As = smem, *Bs = smem + 2 * L_TILE;       // [2][L_TILE] each
+  __shared__ __attribute__((aligned(16))) bf16 As0[L_TILE], As1[L_TILE], Bs0[L_TILE], Bs1[L_TILE];   // 128 KB
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
@@ -216,10 +208,9 @@ __global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict_
   const int m0 = tile_m * LM;
 
   const bf16 *a_src[4], *b_src[4];
-  int st_off[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int c = tid + 512 * i, row = c >> 3, chunk = c & 7;
+    const int c = tid + 512 * i, row = c >> 3, chunk = (c & 7) ^ ((row >> 1) & 7);   // swizzle on the global side
     int am = m0 + row;
     am = am < M ? am : M - 1;
     a_src[i] = A + (size_t)am * K + chunk * 8;
@@ -232,7 +223,6 @@ __global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict_
       bn = tile_n * LN + row;
     }
     b_src[i] = B + (size_t)bn * K + chunk * 8;
-    st_off[i] = lds_off(row, chunk);
   }
 
   f32x16 acc[4][2];
@@ -245,19 +235,13 @@ __global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict_
 
   const int nk = K / BK, last = nk - 1;
   const int frag_row = lane & 31, frag_half = lane >> 5;
-  u32x4 ra[4], rb[4];
-  auto gload = [&](int kt) {
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma = [&](int buf, int kt) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      ra[i] = *(const u32x4 *)(a_src[i] + (size_t)kt * BK);
-      rb[i] = *(const u32x4 *)(b_src[i] + (size_t)kt * BK);
-    }
-  };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *(u32x4 *)&As[buf * L_TILE + st_off[i]] = ra[i];
-      *(u32x4 *)&Bs[buf * L_TILE + st_off[i]] = rb[i];
+      const int slot = (i * 8 + wave_u) * 512;
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * BK), LDS_PTR((buf ? As1 : As0) + slot), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src[i] + (size_t)kt * BK), LDS_PTR((buf ? Bs1 : Bs0) + slot), 16, 0, 0);
     }
   };
   auto compute = [&](int buf) {
@@ -265,10 +249,10 @@ __global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict_
     auto frags = [&](int slot, int kk) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        fa[slot][i] = *(const bf16x8 *)&As[buf * L_TILE + lds_off(wm * 128 + i * 32 + frag_row, kk * 2 + frag_half)];
+        fa[slot][i] = *(const bf16x8 *)&(buf ? As1 : As0)[lds_off(wm * 128 + i * 32 + frag_row, kk * 2 + frag_half)];
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        fb[slot][j] = *(const bf16x8 *)&Bs[buf * L_TILE + lds_off(wn * 64 + j * 32 + frag_row, kk * 2 + frag_half)];
+        fb[slot][j] = *(const bf16x8 *)&(buf ? Bs1 : Bs0)[lds_off(wn * 64 + j * 32 + frag_row, kk * 2 + frag_half)];
     };
     frags(0, 0);
 #pragma unroll
@@ -283,18 +267,22 @@ __global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict_
     }
   };
 
-  // One K-step ahead in registers: the loads of step kt+1 are issued before the MFMAs of step kt and
-  // written to the other LDS stage after them (branch-free body, see the small-tile kernel).
-  gload(0);
-  lstore(0);
+  // The loads of step kt+1 stream into the other LDS stage while step kt is multiplied out
+  // (branch-free body, see the small-tile kernel).
+  dma(0, 0);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    gload(min(kt + 1, last));
+  int kt = 0;
+  for (; kt + 2 <= nk; kt += 2) {
+    dma(1, kt + 1);
     __builtin_amdgcn_sched_barrier(0);
-    compute(kt & 1);
-    lstore((kt + 1) & 1);
+    compute(0);
+    __syncthreads();
+    dma(0, min(kt + 2, last));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(1);
     __syncthreads();
   }
+  if (kt < nk) compute(0);
 
   if (EPI == ARB_EPI_SWIGLU_BF16) {
     bf16 *C = (bf16 *)Cv;
@@ -367,17 +355,7 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   if (splits == 1 && big_tiles >= kBigTileMinTiles && 5 * big_tiles >= 4 * 256 * ceil_div(big_tiles, 256)) {
     const int tm = ceil_div(M, LM), tn = N / big_n;
     const dim3 bgrid(tm * tn), bblock(512);
-    const size_t lds = 4 * L_TILE * sizeof(bf16);
-    static bool attr_set[3] = {false, false, false};
-#define ARB_BIG(E)                                                                                             \
-  do {                                                                                                         \
-    if (!attr_set[E]) {                                                                                        \
-      ARB_CHECK_HIP(hipFuncSetAttribute((const void *)gemm256_kernel<E>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                        (int)lds));                                                            \
-      attr_set[E] = true;                                                                                      \
-    }                                                                                                          \
-    hipLaunchKernelGGL((gemm256_kernel<E>), bgrid, bblock, lds, st, A, B, C, M, N, K, tm, tn);                 \
-  } while (0)
+#define ARB_BIG(E) hipLaunchKernelGGL((gemm256_kernel<E>), bgrid, bblock, 0, st, A, B, C, M, N, K, tm, tn)
     switch (epilogue) {
       case ARB_EPI_STORE_BF16: ARB_BIG(ARB_EPI_STORE_BF16); break;
       case ARB_EPI_RESIDUAL_F32: ARB_BIG(ARB_EPI_RESIDUAL_F32); break;
