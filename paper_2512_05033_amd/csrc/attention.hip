@@ -8,8 +8,9 @@
 // streamed from HBM once per 128 rows that need it; rows of different query
 // tiles of the same (b, hk) meet in L2.
 //
-// Per 64-key tile, K and V go to LDS row-major [key][hd] with XOR-swizzled
-// 16-byte chunks.  S^T = K Q^T (keys are MFMA rows, queries are columns), so a
+// Per 64-key tile, K and V stream into LDS row-major [key][hd] (XOR-swizzled
+// 16-byte chunks) by direct-to-LDS global loads, double-buffered: tile t+1 is in
+// flight while tile t is multiplied out.  S^T = K Q^T (keys are MFMA rows, queries are columns), so a
 // lane owns one query column: the row max / row sum are in-lane reductions plus
 // one cross-half shuffle, and exp2(S^T - m) is already laid out as the B operand
 // of O^T = V^T P^T.  The V^T fragments (a lane needs 8 keys of one hd column) come
@@ -31,11 +32,8 @@ constexpr int KT = 64;         // keys per tile
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-template <int HD>
-struct Smem {
-  __attribute__((aligned(16))) bf16 k[KT * HD];
-  __attribute__((aligned(16))) bf16 v[KT * HD];
-};
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 template <int HD>
 __device__ __forceinline__ int kv_off(int key, int chunk) {   // element offset of a 16-byte chunk of a key row
@@ -46,7 +44,7 @@ __device__ __forceinline__ int kv_off(int key, int chunk) {   // element offset 
 
 // One 64-key tile for one wave: scores, online softmax update, O^T accumulation.
 template <int HD>
-__device__ __forceinline__ void attend_tile(const Smem<HD> &sm, const bf16x8 (&qf)[HD / 16], f32x16 (&o)[HD / 32],
+__device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, const bf16x8 (&qf)[HD / 16], f32x16 (&o)[HD / 32],
                                             float &m_run, float &l_run, int ts, int limit, float scale_log2, int col,
                                             int half, int lane) {
   constexpr int KSTEPS = HD / 16, MT = HD / 32;
@@ -57,7 +55,7 @@ __device__ __forceinline__ void attend_tile(const Smem<HD> &sm, const bf16x8 (&q
     for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
-      const bf16x8 kf = *(const bf16x8 *)&sm.k[kv_off<HD>(t * 32 + col, kk * 2 + half)];
+      const bf16x8 kf = *(const bf16x8 *)&sk[kv_off<HD>(t * 32 + col, kk * 2 + half)];
       st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
     }
   }
@@ -106,8 +104,8 @@ __device__ __forceinline__ void attend_tile(const Smem<HD> &sm, const bf16x8 (&q
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int c = mt * 32 + vcol;
-        const bf16 *a0 = &sm.v[kv_off<HD>(key0, c >> 3) + (c & 7)];
-        const bf16 *a1 = &sm.v[kv_off<HD>(key0 + 8, c >> 3) + (c & 7)];
+        const bf16 *a0 = &sv[kv_off<HD>(key0, c >> 3) + (c & 7)];
+        const bf16 *a1 = &sv[kv_off<HD>(key0 + 8, c >> 3) + (c & 7)];
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a0);
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a1);
         union { s16x4 s[2]; bf16x8 b; } vf;
@@ -122,16 +120,30 @@ template <int HD, bool SPLIT>
 __global__ __launch_bounds__(256, 2) void attention_kernel(
     const bf16 *__restrict__ q, int q_row_stride, const bf16 *__restrict__ k_pool, const bf16 *__restrict__ v_pool,
     const int32_t *__restrict__ block_tables, int max_blocks, const int32_t *__restrict__ prefix_lens,
-    const int32_t *__restrict__ cu, int T, int Hq, int Hkv, int max_qtiles, int kv_chunk, float scale_log2,
-    bf16 *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml) {
+    const int32_t *__restrict__ cu, int T, int Hq, int Hkv, int max_qtiles, int max_splits, int kv_chunk,
+    float scale_log2, bf16 *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml) {
   constexpr int CPK = HD / 8;              // 16-byte chunks per key
-  constexpr int LOADS = KT * CPK / 256;    // chunks per thread per operand per tile
+  constexpr int LOADS = KT * CPK / 256;    // wave-wide 1 KB loads per wave, operand and tile
+  constexpr int KPL = 64 / CPK;            // keys covered by one wave-wide load (4 or 8: inside one block)
   constexpr int KSTEPS = HD / 16;          // MFMA k-steps over the head dimension
   constexpr int MT = HD / 32;              // 32-row tiles of O^T
-  __shared__ Smem<HD> sm;
+  // Two stages of K and V; one array per stage so that LDS reads of one stage are not ordered
+  // behind the direct-to-LDS loads in flight into the other.
+  __shared__ __attribute__((aligned(16))) bf16 K0[KT * HD], K1[KT * HD], V0[KT * HD], V1[KT * HD];
 
-  const int split = blockIdx.x, b = blockIdx.z;
-  const int hk = blockIdx.y / max_qtiles, qtile = blockIdx.y - hk * max_qtiles;
+  // Work item of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a
+  // contiguous range of items, ordered so that the query tiles that stream the same keys (same
+  // sequence, kv head and split) are neighbours and meet in that XCD's L2.
+  int item;
+  {
+    const int total = gridDim.x, per = total / 8, rem = total % 8;
+    const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
+    item = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + j;
+  }
+  const int qtile = item % max_qtiles; item /= max_qtiles;
+  const int split = item % max_splits; item /= max_splits;
+  const int hk = item % Hkv;
+  const int b = item / Hkv;
   const int G = Hq / Hkv;
   const int p = prefix_lens[b], tok0 = cu[b], s = cu[b + 1] - tok0;
   const int rows = s * G, row0 = qtile * QROWS;
@@ -142,7 +154,6 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
   if (kv_begin >= visible) return;
   const int kv_end = min(visible, kv_begin + kv_chunk);
   const int ctx = p + s;
-  const int n_blk = (ctx + ARB_KV_BLOCK - 1) / ARB_KV_BLOCK;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
@@ -176,42 +187,58 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
     for (int r = 0; r < 16; ++r) o[mt][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
+  // Tile loads.  One wave-wide direct-to-LDS load moves KPL whole keys (1 KB) of one 16-key block:
+  // the block id is wave-uniform (scalar), lane l lands in chunk slot l % CPK of key l / CPK and
+  // fetches the logical chunk that the read-side swizzle expects there.  Keys past the context
+  // re-read the last valid key (finite data; they are masked out of the softmax anyway), so every
+  // address is in bounds and the loop body needs no branch.
   const int32_t *table = block_tables + (size_t)b * max_blocks;
-  u32x4 rk[LOADS], rv[LOADS];
-
-  // Keys past the context are never visible, but their V rows are zeroed so that a
-  // zero probability cannot meet a non-finite stale value.
-  auto load_tile = [&](int tile_start) {
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int last_key = ctx - 1, last_blk = last_key / ARB_KV_BLOCK;
+  const int n_tiles = (kv_end - kv_begin + KT - 1) / KT;
+  const int lkey = lane / CPK, pchunk = lane % CPK;
+  int blk_id[LOADS];                       // pool block of each load of the tile to be issued next
+  auto lookup = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int c = tid + 256 * i, key = c / CPK, chunk = c - key * CPK;
-      const int j = tile_start + key, bi = j / ARB_KV_BLOCK;
-      if (bi < n_blk) {
-        const size_t base = (((size_t)table[bi] * Hkv + hk) * ARB_KV_BLOCK + (j % ARB_KV_BLOCK)) * HD + chunk * 8;
-        rk[i] = *(const u32x4 *)(k_pool + base);
-        rv[i] = j < ctx ? *(const u32x4 *)(v_pool + base) : u32x4{0, 0, 0, 0};
-      } else {
-        rk[i] = u32x4{0, 0, 0, 0};
-        rv[i] = u32x4{0, 0, 0, 0};
-      }
+      const int key0 = kv_begin + tile * KT + (i * 4 + wave_u) * KPL;
+      blk_id[i] = table[min(key0 / ARB_KV_BLOCK, last_blk)];
     }
   };
-  auto store_tile = [&]() {
+  auto dma = [&](bf16 *dk, bf16 *dv, int tile) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int c = tid + 256 * i, key = c / CPK, chunk = c - key * CPK;
-      *(u32x4 *)&sm.k[kv_off<HD>(key, chunk)] = rk[i];
-      *(u32x4 *)&sm.v[kv_off<HD>(key, chunk)] = rv[i];
+      const int g = i * 4 + wave_u;                                  // 1 KB slot of the tile
+      const int tkey = g * KPL + lkey;                               // tile-local key of this lane
+      const int j = min(kv_begin + tile * KT + tkey, last_key);
+      const int blk = min((kv_begin + tile * KT + g * KPL) / ARB_KV_BLOCK, last_blk);
+      const int chunk = pchunk ^ (HD == 128 ? (tkey & 15) : ((tkey >> 1) & 7));
+      const size_t src = (((size_t)blk_id[i] * Hkv + hk) * ARB_KV_BLOCK + (j - blk * ARB_KV_BLOCK)) * HD + chunk * 8;
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(k_pool + src), LDS_PTR(dk + g * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(v_pool + src), LDS_PTR(dv + g * 512), 16, 0, 0);
     }
   };
 
-  load_tile(kv_begin);
-  for (int ts = kv_begin; ts < kv_end; ts += KT) {
-    __syncthreads();                 // previous tile's reads are done
-    store_tile();
+  // Tile t is multiplied out of one stage while tile t+1 streams into the other and the block ids
+  // of tile t+2 are looked up; the barrier that ends a step also waits for the loads.
+  const int last_tile = n_tiles - 1;
+  lookup(0);
+  dma(K0, V0, 0);
+  lookup(min(1, last_tile));
+  __syncthreads();
+  for (int t = 0; t < n_tiles; t += 2) {
+    dma(K1, V1, min(t + 1, last_tile));
+    lookup(min(t + 2, last_tile));
+    __builtin_amdgcn_sched_barrier(0);
+    if (wave_active) attend_tile<HD>(K0, V0, qf, o, m_run, l_run, kv_begin + t * KT, limit, scale_log2, col, half, lane);
     __syncthreads();
-    if (ts + KT < kv_end) load_tile(ts + KT);
-    if (wave_active) attend_tile<HD>(sm, qf, o, m_run, l_run, ts, limit, scale_log2, col, half, lane);
+    if (t + 1 < n_tiles) {
+      dma(K0, V0, min(t + 2, last_tile));
+      lookup(min(t + 3, last_tile));
+      __builtin_amdgcn_sched_barrier(0);
+      if (wave_active) attend_tile<HD>(K1, V1, qf, o, m_run, l_run, kv_begin + (t + 1) * KT, limit, scale_log2, col, half, lane);
+      __syncthreads();
+    }
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -340,11 +367,11 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
     }
   }
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)head_dim));
-  const dim3 grid(plan.max_splits, n_kv_heads * plan.max_qtiles, batch), block(256);
+  const dim3 grid(batch * n_kv_heads * plan.max_splits * plan.max_qtiles), block(256);
 #define ARB_ATTN_LAUNCH(HD, SPLIT)                                                                                 \
   hipLaunchKernelGGL((attention_kernel<HD, SPLIT>), grid, block, 0, st, q, q_row_stride, k_pool, v_pool,           \
                      block_tables, max_blocks_per_seq, prefix_lens, cu_step_lens, total_tokens, n_q_heads,         \
-                     n_kv_heads, plan.max_qtiles, plan.kv_chunk, scale_log2, out, part_acc, part_ml)
+                     n_kv_heads, plan.max_qtiles, plan.max_splits, plan.kv_chunk, scale_log2, out, part_acc, part_ml)
   if (head_dim == 128) { if (split) ARB_ATTN_LAUNCH(128, true); else ARB_ATTN_LAUNCH(128, false); }
   else                 { if (split) ARB_ATTN_LAUNCH(64, true);  else ARB_ATTN_LAUNCH(64, false); }
 #undef ARB_ATTN_LAUNCH
