@@ -50,31 +50,46 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
   constexpr int KSTEPS = HD / 16, MT = HD / 32;
   f32x16 st[2];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
+  for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
+  {
+    // K fragments of step kk+1 are read while the MFMAs of step kk run
+    bf16x8 kf[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) kf[0][t] = *(const bf16x8 *)&sk[kv_off<HD>(t * 32 + col, half)];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
-      const bf16x8 kf = *(const bf16x8 *)&sk[kv_off<HD>(t * 32 + col, kk * 2 + half)];
-      st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
+      if (kk + 1 < KSTEPS) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          kf[(kk + 1) & 1][t] = *(const bf16x8 *)&sk[kv_off<HD>(t * 32 + col, (kk + 1) * 2 + half)];
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][t], qf[kk], st[t], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+  }
+  // Causal mask (it also hides keys past the context): only tiles that reach some row's limit pay
+  // for it.  Register r of tile t holds key ts + 32t + 8(r/4) + 4*half + r%4.
+  const int vis = limit - ts - 4 * half;
+  if (__builtin_amdgcn_ballot_w64(vis < KT - 1) != 0) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st[t][r] = (t * 32 + 8 * (r >> 2) + (r & 3)) <= vis ? st[t][r] : -INFINITY;
   }
   // running max over the raw logits (the positive scale commutes with max)
   float mx = -INFINITY;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      // causal limit of this lane's query row (also hides keys past the context)
-      const int j = ts + t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-      st[t][r] = j <= limit ? st[t][r] : -INFINITY;
-      mx = fmaxf(mx, st[t][r]);
-    }
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[t][r]);
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
   const float m_new = fmaxf(m_run, mx * scale_log2);
   const float m_use = m_new == -INFINITY ? 0.f : m_new;
   if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {     // some row's max moved: rescale the state
-    const float alpha = exp2f(m_run - m_use);                // m_run = -inf -> 0
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
     l_run *= alpha;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -88,7 +103,7 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const float pv = exp2f(fmaf(st[t][r], scale_log2, -m_use));
+      const float pv = __builtin_amdgcn_exp2f(fmaf(st[t][r], scale_log2, -m_use));   // raw v_exp_f32; -inf -> 0
       l_add += pv;
       pf[t][r >> 3][r & 7] = (bf16)pv;
     }
