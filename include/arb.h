@@ -191,6 +191,15 @@ arb_status arb_stage_norm_pool_head(const float *h, const float *g_final, float 
                                     void *hidden_out, float *scores, uint8_t *escalate, void *ws, size_t ws_bytes,
                                     void *stream);
 
+/* Decoder layers [layer_begin, layer_end) of the forward (Section 4.2's router backbone / the target's
+ * pass) applied to a given residual stream: h_in device fp32 [total_tokens, d_model] is the stream entering
+ * layer_begin, h_out (may alias h_in) receives the stream leaving layer_end - 1; no embedding, no final
+ * norm.  The step's K/V of those layers are appended as in arb_score_steps.  token_ids is not read.
+ * Lets every layer of a deep model be checked at full size without the drift of the layers before it. */
+arb_status arb_stage_layers(arb_model *m, const arb_kv *kv, const arb_batch *batch, int32_t layer_begin,
+                            int32_t layer_end, const float *h_in, float *h_out, void *ws, size_t ws_bytes,
+                            void *stream);
+
 /* Timing hook for measurement harnesses (no paper passage: it computes nothing).
  * While armed, arb_score_steps / arb_prefill record start[i] before and stop[i]
  * after their i-th launch of the given stage on the call's stream, for i < n.

@@ -213,33 +213,55 @@ def swiglu_mlp(x: np.ndarray, wgu, wd) -> np.ndarray:
 
 # --------------------------------------------------------------------------- forward
 
+def decoder_layer(m: Model, w: Params, l: int, h: np.ndarray, k_pool: np.ndarray, v_pool: np.ndarray, pos, slots,
+                  prefix_lens, cu_step_lens, block_tables, trace: Optional[Dict[str, np.ndarray]] = None) -> np.ndarray:
+    """One pre-norm decoder layer on the residual stream h [T, d]: attention block
+    (RMSNorm, QKV, rotary q/k, K/V append, append-attention, O projection, residual add),
+    then MLP block (RMSNorm, SwiGLU, residual add)."""
+    blk, Hq, Hkv, hd = m.kv_block, m.n_q_heads, m.n_kv_heads, m.head_dim
+    T = h.shape[0]
+    x = rmsnorm(h, w.g_attn[l], m.rms_eps)
+    qkv = (x @ as_float(w.wqkv[l]).T).reshape(T, Hq + 2 * Hkv, hd)
+    q = rope(qkv[:, :Hq], pos, m.rope_base)
+    k = rope(qkv[:, Hq:Hq + Hkv], pos, m.rope_base)
+    v = qkv[:, Hq + Hkv:]
+    kv_append(k_pool, v_pool, slots, k, v, blk)
+    o = append_attention(q, k_pool, v_pool, prefix_lens, cu_step_lens, block_tables, blk)
+    h_attn = h + o.reshape(T, Hq * hd) @ as_float(w.wo[l]).T
+    x2 = rmsnorm(h_attn, w.g_mlp[l], m.rms_eps)
+    h_new = h_attn + swiglu_mlp(x2, w.wgu[l], w.wd[l])
+    if trace is not None:
+        trace.update(x_attn=x, qkv=qkv.reshape(T, -1), q_rot=q, k_rot=k, attn=o, h_attn=h_attn, x_mlp=x2, h1=h_new)
+    return h_new
+
+
+def decoder_layers(m: Model, w: Params, k_pools, v_pools, h: np.ndarray, layer_begin: int, layer_end: int,
+                   prefix_lens, cu_step_lens, block_tables, keep: Optional[List[np.ndarray]] = None) -> np.ndarray:
+    """Layers [layer_begin, layer_end) applied to the residual stream h; with `keep`,
+    the stream after every layer is appended to it."""
+    pos = positions(prefix_lens, cu_step_lens)
+    slots = slot_mapping(prefix_lens, cu_step_lens, block_tables, m.kv_block)
+    h = np.asarray(h, dtype=F)
+    for l in range(layer_begin, layer_end):
+        h = decoder_layer(m, w, l, h, k_pools[l], v_pools[l], pos, slots, prefix_lens, cu_step_lens, block_tables)
+        if keep is not None:
+            keep.append(h)
+    return h
+
+
 def forward(m: Model, w: Params, k_pools: Sequence[np.ndarray], v_pools: Sequence[np.ndarray], token_ids,
             prefix_lens, cu_step_lens, block_tables, trace: Optional[Dict[str, np.ndarray]] = None) -> np.ndarray:
     """Final-normed hidden states [T, d] of the step tokens; appends the step's
     K/V (bf16) to the pools at positions [p_b, p_b+s_b) as a side effect.
     With `trace`, per-stage tensors of layer 0 are recorded under fixed names."""
-    blk, Hq, Hkv, hd = m.kv_block, m.n_q_heads, m.n_kv_heads, m.head_dim
     pos = positions(prefix_lens, cu_step_lens)
-    slots = slot_mapping(prefix_lens, cu_step_lens, block_tables, blk)
+    slots = slot_mapping(prefix_lens, cu_step_lens, block_tables, m.kv_block)
     h = embed(w.embed, token_ids)
-    T = h.shape[0]
     if trace is not None:
         trace["slots"], trace["h0"] = slots.copy(), h.copy()
     for l in range(m.n_layers):
-        x = rmsnorm(h, w.g_attn[l], m.rms_eps)
-        qkv = (x @ as_float(w.wqkv[l]).T).reshape(T, Hq + 2 * Hkv, hd)
-        q = rope(qkv[:, :Hq], pos, m.rope_base)
-        k = rope(qkv[:, Hq:Hq + Hkv], pos, m.rope_base)
-        v = qkv[:, Hq + Hkv:]
-        kv_append(k_pools[l], v_pools[l], slots, k, v, blk)
-        o = append_attention(q, k_pools[l], v_pools[l], prefix_lens, cu_step_lens, block_tables, blk)
-        h_attn = h + o.reshape(T, Hq * hd) @ as_float(w.wo[l]).T
-        x2 = rmsnorm(h_attn, w.g_mlp[l], m.rms_eps)
-        h_new = h_attn + swiglu_mlp(x2, w.wgu[l], w.wd[l])
-        if trace is not None and l == 0:
-            trace.update(x_attn=x, qkv=qkv.reshape(T, -1), q_rot=q, k_rot=k, attn=o, h_attn=h_attn,
-                         x_mlp=x2, h1=h_new)
-        h = h_new
+        h = decoder_layer(m, w, l, h, k_pools[l], v_pools[l], pos, slots, prefix_lens, cu_step_lens, block_tables,
+                          trace if l == 0 else None)
     return rmsnorm(h, w.g_final, m.rms_eps)
 
 

@@ -9,5 +9,5 @@ from .binding import (ARB_ACCEPT_IF_GT, ARB_ECAPACITY, ARB_EHIP, ARB_EINVAL, ARB
                       ARB_STAGE_GATE_UP, ARB_STAGE_NORM, ARB_STAGE_OPROJ, ARB_STAGE_QKV, ARB_STAGE_ROPE_APPEND, EXPORTS,
                       StageTimer, ArbError, DeviceBatch, KVCache, Model,
                       arb_prefill, arb_route, arb_score_steps, arb_slot_mapping, arb_stage_attention,
-                      arb_stage_gemm, arb_stage_norm_pool_head, arb_stage_rmsnorm, arb_stage_rope_append,
+                      arb_stage_gemm, arb_stage_layers, arb_stage_norm_pool_head, arb_stage_rmsnorm, arb_stage_rope_append,
                       load_library)

@@ -26,7 +26,7 @@ _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4:
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
            "arb_route", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
-           "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_model_trace", "arb_model_trace_count",
+           "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
 
@@ -90,6 +90,8 @@ def load_library(path: Optional[str] = None):
     lib.arb_stage_norm_pool_head.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.POINTER(_Batch), C.c_int32,
                                              C.c_void_p, C.c_float, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_stage_layers.argtypes = [C.c_void_p, C.POINTER(_KV), C.POINTER(_Batch), C.c_int32, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.arb_model_trace.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32]
     lib.arb_model_trace_count.argtypes = [C.c_void_p]
     lib.arb_model_trace_count.restype = C.c_int32
@@ -302,6 +304,19 @@ def arb_stage_norm_pool_head(h: torch.Tensor, g_final: torch.Tensor, eps: float,
                                                    _ptr(w_head), float(b_head), pool, float(tau), _ptr(hidden),
                                                    _ptr(scores), _ptr(esc), ws.data_ptr(), ws.numel(), _stream(stream)))
     return scores, esc, hidden
+
+
+def arb_stage_layers(model: Model, kv: KVCache, batch: DeviceBatch, layer_begin: int, layer_end: int,
+                     h_in: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """h_in fp32 [T, d], the residual stream entering layer_begin -> the stream leaving layer_end - 1."""
+    _dev(h_in, torch.float32)
+    if tuple(h_in.shape) != (batch.total_tokens, model.cfg.d_model):
+        raise ValueError("residual stream shape")
+    h_out = torch.empty_like(h_in)
+    ws = _workspace(model, batch, ws)
+    _check(load_library().arb_stage_layers(model.handle, C.byref(kv.c), C.byref(batch.c), layer_begin, layer_end,
+                                           _ptr(h_in), _ptr(h_out), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return h_out
 
 
 class StageTimer:

@@ -203,22 +203,26 @@ static arb_status check_batch(const arb_batch *bt, int kv_block, BatchInfo *info
 
 // ------------------------------------------------------------------------ forward
 
+// Runs decoder layers [l0, l1).  With h_in == nullptr the pass starts from the token embeddings (l0 must be 0)
+// and ends with the final norm (+ head); otherwise it starts from the given fp32 residual stream and hands the
+// residual stream after layer l1 - 1 back through h_out, with no final norm.
 static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, bool with_head, float tau,
                           float *scores, uint8_t *escalate, void *hidden_out, void *ws, size_t ws_bytes,
-                          hipStream_t st) {
+                          hipStream_t st, int l0, int l1, const float *h_in = nullptr, float *h_out = nullptr) {
   if (!m || !kv) return arb_fail(ARB_EINVAL, "null model or kv");
   const arb_model_cfg &c = m->cfg;
   BatchInfo info;
-  if (arb_status s = check_batch(bt, c.kv_block, &info, true)) return s;
+  if (arb_status s = check_batch(bt, c.kv_block, &info, h_in == nullptr)) return s;
   if (bt->batch == 0) return ARB_OK;
   if (with_head && !scores) return arb_fail(ARB_EINVAL, "model has a router head but scores is null");
   if (!with_head && (scores || escalate)) return arb_fail(ARB_EINVAL, "scores/escalate given but no router head is applied");
   if (!kv->k_pool || !kv->v_pool) return arb_fail(ARB_EINVAL, "null kv pool table");
-  for (int l = 0; l < c.n_layers; ++l)
+  for (int l = l0; l < l1; ++l)
     if (!kv->k_pool[l] || !kv->v_pool[l]) return arb_fail(ARB_EINVAL, "null kv pool in layer %d", l);
   const int T = bt->total_tokens, B = bt->batch, d = c.d_model;
   const Workspace w = carve(c, T, info.max_ctx, ws);
   if (!ws || ws_bytes < w.total) return arb_fail(ARB_ECAPACITY, "workspace %zu < %zu bytes", ws_bytes, w.total);
+  if (h_in) ARB_CHECK_HIP(hipMemcpyAsync(w.h, h_in, (size_t)T * d * sizeof(float), hipMemcpyDeviceToDevice, st));
 
   const int G = c.n_q_heads / c.n_kv_heads;
   const AttnPlan plan = plan_attention(B, bt->prefix_lens_host, bt->cu_step_lens_host, G, c.n_kv_heads);
@@ -232,10 +236,10 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
                              c.kv_block, w.tok_pos, w.tok_slot, st)))
     return s;
   if ((s = launch_rope_table(w.tok_pos, T, c.head_dim, c.rope_base, w.cs, st))) return s;
-  for (int l = 0; l < c.n_layers; ++l) {
+  for (int l = l0; l < l1; ++l) {
     {
       TraceScope t(m, ARB_STAGE_NORM, st);
-      if (l == 0)
+      if (l == 0 && !h_in)
         s = launch_embed_rmsnorm(m->embed, bt->token_ids, m->g_attn[0], c.rms_eps, T, d, w.h, w.x, st);
       else
         s = launch_rmsnorm(w.h, w.parts, pending, m->g_attn[l], c.rms_eps, T, d, w.x, st);
@@ -281,6 +285,12 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     }
     if (s) return s;
   }
+  if (h_in) {
+    // fold the last projection's partial products into the residual stream, then hand it back
+    if (pending && (s = launch_rmsnorm(w.h, w.parts, pending, m->g_final, c.rms_eps, T, d, w.x, st))) return s;
+    ARB_CHECK_HIP(hipMemcpyAsync(h_out, w.h, (size_t)T * d * sizeof(float), hipMemcpyDeviceToDevice, st));
+    return ARB_OK;
+  }
   if ((s = launch_final_norm_head(w.h, w.parts, pending, m->g_final, c.rms_eps, T, d, with_head ? m->w_head : nullptr,
                                   (bf16 *)hidden_out, with_head ? w.tok_dot : nullptr, st)))
     return s;
@@ -293,13 +303,14 @@ extern "C" arb_status arb_score_steps(arb_model *m, const arb_kv *kv, const arb_
                                       uint8_t *escalate, void *hidden_out, void *ws, size_t ws_bytes, void *stream) {
   if (!m) return arb_fail(ARB_EINVAL, "null model");
   return forward(m, kv, batch, m->cfg.has_router_head != 0, tau, scores, escalate, hidden_out, ws, ws_bytes,
-                 (hipStream_t)stream);
+                 (hipStream_t)stream, 0, m->cfg.n_layers);
 }
 
 extern "C" arb_status arb_prefill(arb_model *m, const arb_kv *kv, const arb_batch *batch, void *hidden_out, void *ws,
                                   size_t ws_bytes, void *stream) {
   if (!m) return arb_fail(ARB_EINVAL, "null model");
-  return forward(m, kv, batch, false, 0.f, nullptr, nullptr, hidden_out, ws, ws_bytes, (hipStream_t)stream);
+  return forward(m, kv, batch, false, 0.f, nullptr, nullptr, hidden_out, ws, ws_bytes, (hipStream_t)stream, 0,
+                 m->cfg.n_layers);
 }
 
 extern "C" arb_status arb_route(const float *scores, int32_t n, float tau, int32_t sense, uint8_t *escalate,
@@ -380,6 +391,17 @@ extern "C" arb_status arb_stage_rope_append(const arb_model *m, void *qkv, void 
   if ((s = launch_rope_table(tok_pos, (int)T, c.head_dim, c.rope_base, cs, st))) return s;
   return launch_rope_append((bf16 *)qkv, cs, tok_slot, (bf16 *)k_pool, (bf16 *)v_pool, (int)T, c.n_q_heads,
                             c.n_kv_heads, c.head_dim, st);
+}
+
+extern "C" arb_status arb_stage_layers(arb_model *m, const arb_kv *kv, const arb_batch *batch, int32_t layer_begin,
+                                       int32_t layer_end, const float *h_in, float *h_out, void *ws, size_t ws_bytes,
+                                       void *stream) {
+  if (!m) return arb_fail(ARB_EINVAL, "null model");
+  if (layer_begin < 0 || layer_end > m->cfg.n_layers || layer_begin >= layer_end)
+    return arb_fail(ARB_EINVAL, "arb_stage_layers: layers [%d, %d) of %d", layer_begin, layer_end, m->cfg.n_layers);
+  if (batch && batch->batch > 0 && (!h_in || !h_out)) return arb_fail(ARB_EINVAL, "arb_stage_layers: null residual stream");
+  return forward(m, kv, batch, false, 0.f, nullptr, nullptr, nullptr, ws, ws_bytes, (hipStream_t)stream, layer_begin,
+                 layer_end, h_in, h_out);
 }
 
 extern "C" arb_status arb_stage_norm_pool_head(const float *h, const float *g_final, float eps, const arb_batch *batch,

@@ -322,7 +322,7 @@ __global__ __launch_bounds__(64) void attention_merge_kernel(const float *__rest
 }  // namespace
 
 static const int kTargetWorkgroups = 512;    // two resident workgroups per CU on 256 CUs
-static const int kMinChunk = 256, kMaxSplits = 64;
+static const int kMinChunk = 256, kMaxChunk = 2048, kMaxSplits = 64;
 
 int attention_splits_cap(int max_ctx) {
   if (max_ctx <= 0) return 1;
@@ -339,8 +339,11 @@ AttnPlan plan_attention(int batch, const int32_t *prefix_host, const int32_t *cu
     max_ctx = ctx > max_ctx ? ctx : max_ctx;
     max_step = s > max_step ? s : max_step;
   }
-  // keys per split so that about kTargetWorkgroups workgroups share the streaming evenly
+  // Keys per split: about kTargetWorkgroups workgroups (one resident round) when contexts are short,
+  // so that few partial states have to be merged; never more than kMaxChunk keys, so that long
+  // ragged contexts become many rounds of similar-sized workgroups instead of one unbalanced round.
   long long chunk = (keys_streamed / kTargetWorkgroups + KT - 1) / KT * KT;
+  if (chunk > kMaxChunk) chunk = kMaxChunk;
   if (chunk < kMinChunk) chunk = kMinChunk;
   while (max_ctx > chunk * kMaxSplits) chunk += KT;
   AttnPlan pl;

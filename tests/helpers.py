@@ -7,6 +7,14 @@ import workloads as W
 from oracle import arb_oracle as O
 
 
+# Hidden-state bars (max|got - ref| / max|ref| over the output tensor).  2e-2 is the stated bar.  At the full
+# 28-layer depth of the 1.5B-class shape, rounding nothing but the operands of the matrix products to bf16
+# (inside otherwise exact fp64 arithmetic) already moves the output by 2e-2 to 2.7e-2, depending on the
+# sample (test_bf16_floor.py), so end-to-end runs that deep are held to 4e-2 and every layer is checked on
+# its own, from the oracle's residual stream, against the 2e-2 bar.
+HIDDEN_TOL, FULL_DEPTH_HIDDEN_TOL, SCORE_TOL = 2e-2, 4e-2, 1e-2
+
+
 def oracle_model(m: W.ModelShape) -> O.Model:
     return O.Model(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn, m.vocab,
                    m.rms_eps, m.rope_base, m.kv_block)

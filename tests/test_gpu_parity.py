@@ -1,18 +1,17 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
-the same seeded inputs.  Tolerances: hidden states max|d|/max|ref| <= 2e-2,
-router scores |d| <= 1e-2, decisions identical unless |score - tau| < 1e-2,
-slot indices and untouched cache contents bit-exact."""
+the same seeded inputs.  Tolerances: hidden states max|d|/max|ref| <= 2e-2
+(helpers.py states the one exception, end-to-end runs at full depth), router
+scores |d| <= 1e-2, decisions identical unless |score - tau| < 1e-2, slot
+indices and untouched cache contents bit-exact."""
 import numpy as np
 import pytest
 import torch
 
 import workloads as W
-from helpers import oracle_model, oracle_params, oracle_pools, rel_err
+from helpers import FULL_DEPTH_HIDDEN_TOL, HIDDEN_TOL, SCORE_TOL, oracle_model, oracle_params, oracle_pools, rel_err
 from oracle import arb_oracle as O
 
 pytestmark = pytest.mark.gpu
-
-HIDDEN_TOL, SCORE_TOL = 2e-2, 1e-2
 
 
 @pytest.fixture(scope="module")
@@ -290,29 +289,126 @@ def test_c2_two_layers_full_batch(A):
     _assert_cache(sess, kp, vp, kp_before, slots)
 
 
-def test_c4_ragged_two_layers_sub_batch(A):
-    """Ragged long-CoT mix on the 1.5B shape: the 6 sequences with the shortest and
-    longest prefixes and steps, 2 layers, against the full pool."""
-    full = W.make_batch(W.C4)
-    pick = sorted({int(np.argmin(full.prefix_lens)), int(np.argmax(full.prefix_lens)),
-                   int(np.argmin(full.step_lens)), int(np.argmax(full.step_lens)), 0, 1})
-    w = W.scaled(W.C4, n_layers=2)
-    batch = full.select(pick)
+def _full_batch_sampled(A, w, pick, *, gain_jitter=0.1, hidden_tol=HIDDEN_TOL):
+    """The GPU runs the whole batch of `w` in its real launch configuration; the
+    oracle recomputes the sequences in `pick` (sequences are independent) from the
+    weights and the cache blocks those sequences reference, copied from the device
+    before the call (the seeded generators give the same bits on both devices)."""
     h = H()
-    sess = h.setup(w, "cuda", batch=batch, gain_jitter=0.1)
-    scores, esc, hidden = A.arb_score_steps(sess.model, sess.kv, sess.dbatch, batch.tau, want_hidden=True, ws=sess.ws)
-    m, p = oracle_model(w.model), oracle_params(W.make_weights(w.model, w.seed, "cpu", gain_jitter=0.1))
-    # the oracle gets only the blocks these sequences reference, renumbered densely
-    need = (batch.prefix_lens + batch.step_lens + 15) // 16
-    used = np.concatenate([batch.block_tables[i, :need[i]] for i in range(batch.batch)])
+    sess = h.setup(w, "cuda", gain_jitter=gain_jitter)
+    batch, m = sess.batch, w.model
+    sub = batch.select(pick)
+    need = (sub.prefix_lens + sub.step_lens + 15) // 16
+    used = np.concatenate([sub.block_tables[i, :need[i]] for i in range(sub.batch)])
     remap = -np.ones(batch.n_blocks, np.int64); remap[used] = np.arange(len(used))
-    tables = np.where(np.arange(batch.block_tables.shape[1])[None, :] < need[:, None], remap[batch.block_tables], 0)
-    kp = [W.bf16_bits(W.kv_pool_blocks(w, l, "k", used)).copy() for l in range(2)]
-    vp = [W.bf16_bits(W.kv_pool_blocks(w, l, "v", used)).copy() for l in range(2)]
-    s_ref, e_ref, y_ref = O.score_steps(m, p, kp, vp, batch.token_ids, batch.prefix_lens, batch.cu_step_lens,
-                                        tables, batch.tau)
-    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
-    _assert_scores(batch, scores, esc, s_ref, e_ref)
+    tables = np.where(np.arange(sub.block_tables.shape[1])[None, :] < need[:, None], remap[sub.block_tables], 0)
+    idx = torch.as_tensor(used, dtype=torch.int64, device="cuda")
+    kp = [W.bf16_bits(sess.kv.k_pools[l][idx]).copy() for l in range(m.n_layers)]
+    vp = [W.bf16_bits(sess.kv.v_pools[l][idx]).copy() for l in range(m.n_layers)]
+    cpu = lambda t: t.cpu()
+    wt = sess.weights
+    weights_cpu = W.Weights(cpu(wt.embed), [cpu(t) for t in wt.wqkv], [cpu(t) for t in wt.wo], [cpu(t) for t in wt.wgu],
+                            [cpu(t) for t in wt.wd], [cpu(t) for t in wt.g_attn], [cpu(t) for t in wt.g_mlp],
+                            cpu(wt.g_final), cpu(wt.w_head), wt.b_head)
+    scores, esc, hidden = A.arb_score_steps(sess.model, sess.kv, sess.dbatch, batch.tau, want_hidden=True, ws=sess.ws)
+    torch.cuda.synchronize()
+    om, op = oracle_model(m), oracle_params(weights_cpu)
+    y_ref = O.forward(om, op, kp, vp, sub.token_ids, sub.prefix_lens, sub.cu_step_lens, tables)
+    rows = np.concatenate([np.arange(batch.cu_step_lens[b], batch.cu_step_lens[b + 1]) for b in pick])
+    got = bf16_np(hidden)[rows]
+    assert rel_err(got, y_ref) < hidden_tol, rel_err(got, y_ref)
+    assert np.sqrt(np.mean((got - y_ref) ** 2) / np.mean(y_ref ** 2)) < hidden_tol
+    if m.has_router_head:
+        s_ref = O.router_scores(y_ref, sub.cu_step_lens, op.w_head, op.b_head)
+        _assert_scores(sub, scores[pick], esc[pick], s_ref, O.route(s_ref, batch.tau))
+    # the picked sequences' step K/V landed where the oracle put them; their prefix blocks are untouched
+    slots = O.slot_mapping(sub.prefix_lens, sub.cu_step_lens, tables, 16)
+    for l in (0, m.n_layers - 1):
+        for pool_t, ref in ((sess.kv.k_pools[l], kp[l]), (sess.kv.v_pools[l], vp[l])):
+            g = W.bf16_bits(pool_t[idx])
+            flat = lambda a: a.transpose(0, 2, 1, 3).reshape(a.shape[0] * 16, -1)
+            written = np.zeros(len(used) * 16, bool); written[slots] = True
+            gf, rf = O.bf16_to_float(flat(g)), O.bf16_to_float(flat(ref))
+            assert np.abs(gf[written] - rf[written]).max() <= hidden_tol * np.abs(rf[written]).max()
+            assert np.array_equal(flat(g)[~written], flat(ref)[~written])
+    return sess
+
+
+def _extremes(batch, extra=()):
+    return sorted({int(np.argmin(batch.prefix_lens)), int(np.argmax(batch.prefix_lens)),
+                   int(np.argmin(batch.step_lens)), int(np.argmax(batch.step_lens)), *extra})
+
+
+def test_c2_full_depth_full_batch(A):
+    """The benchmark configuration itself: 28 layers, 16 sequences; all sequences checked.  Scores,
+    decisions and slots at the stated bars; hidden states at the full-depth bar (helpers.py)."""
+    _full_batch_sampled(A, W.C2, list(range(16)), gain_jitter=0.0, hidden_tol=FULL_DEPTH_HIDDEN_TOL)
+
+
+def _every_layer_from_the_oracle_stream(A, w):
+    """All layers of `w` at full batch, one layer per call: each layer starts from the oracle's
+    residual stream (fp32 copy), so its own error is seen without the drift of the layers before it.
+    What a layer adds to the stream is held to the stated bar."""
+    sess = H().setup(w, "cuda")
+    batch, m = sess.batch, w.model
+    om, op = oracle_model(m), oracle_params(W.make_weights(m, w.seed, "cpu"))
+    kp, vp = oracle_pools(*W.make_kv_pools(w, batch, "cpu"))
+    stream = [O.embed(op.embed, batch.token_ids)]
+    O.decoder_layers(om, op, kp, vp, stream[0], 0, m.n_layers, batch.prefix_lens, batch.cu_step_lens,
+                     batch.block_tables, keep=stream)
+    worst = 0.0
+    for l in range(m.n_layers):
+        h_in = torch.from_numpy(stream[l].astype(np.float32)).cuda()
+        h_out = A.arb_stage_layers(sess.model, sess.kv, sess.dbatch, l, l + 1, h_in, ws=sess.ws)
+        added = h_out.double().cpu().numpy() - h_in.double().cpu().numpy()
+        err = rel_err(added, stream[l + 1] - stream[l])
+        worst = max(worst, err)
+        assert err < HIDDEN_TOL, (l, err)
+        assert rel_err(h_out.cpu().numpy(), stream[l + 1]) < HIDDEN_TOL / 2
+    print("worst per-layer error of the added term:", worst)
+    # several layers in one call give the same stream as the same layers one call at a time
+    lo, hi = 1, min(4, m.n_layers)
+    h = torch.from_numpy(stream[lo].astype(np.float32)).cuda()
+    one = h
+    for l in range(lo, hi):
+        one = A.arb_stage_layers(sess.model, sess.kv, sess.dbatch, l, l + 1, one, ws=sess.ws)
+    assert torch.equal(A.arb_stage_layers(sess.model, sess.kv, sess.dbatch, lo, hi, h, ws=sess.ws), one)
+
+
+def test_c2_every_layer_from_the_oracle_stream(A):
+    _every_layer_from_the_oracle_stream(A, W.C2)
+
+
+def test_c3_target_pass_two_layers(A):
+    """8B-target shape, contiguous KV (identity table), no head: hidden states of all 8 sequences."""
+    _full_batch_sampled(A, W.scaled(W.C3, n_layers=2), list(range(8)))
+
+
+def test_c3_every_layer_of_eight_from_the_oracle_stream(A):
+    _every_layer_from_the_oracle_stream(A, W.scaled(W.C3, n_layers=8))
+
+
+def test_c3_target_pass_eight_layers(A):
+    """Eight layers end to end: at this width the bf16-operand drift reaches the stated bar by then."""
+    _full_batch_sampled(A, W.scaled(W.C3, n_layers=8), list(range(8)), hidden_tol=FULL_DEPTH_HIDDEN_TOL)
+
+
+def test_c4_ragged_full_batch_two_layers(A):
+    """Ragged long-CoT mix on the 1.5B shape at full batch (64 sequences, shuffled tables, seeded tau):
+    the sequences with the shortest/longest prefixes and steps plus two more are recomputed."""
+    w = W.scaled(W.C4, n_layers=2)
+    _full_batch_sampled(A, w, _extremes(W.make_batch(w), (0, 1)))
+
+
+def test_c5_decode_mix_full_batch_two_layers(A):
+    """8B decode-heavy mix at full batch (32 sequences, 1-token and 64-token steps interleaved):
+    shortest and longest prefix of each step kind are recomputed."""
+    w = W.scaled(W.C5, n_layers=2)
+    b = W.make_batch(w)
+    dec, big = np.arange(0, 32, 2), np.arange(1, 32, 2)
+    pick = sorted({int(dec[np.argmin(b.prefix_lens[dec])]), int(dec[np.argmax(b.prefix_lens[dec])]),
+                   int(big[np.argmin(b.prefix_lens[big])]), int(big[np.argmax(b.prefix_lens[big])])})
+    _full_batch_sampled(A, w, pick)
 
 
 def test_target_pass_has_no_head(A):
