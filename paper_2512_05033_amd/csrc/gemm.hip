@@ -33,6 +33,16 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   return base + j;
 }
 
+// Logical tile index -> (tile_m, tile_n): m-tiles in groups of 8, n fastest across groups, so that the
+// tiles an XCD runs at the same time form a compact block (few distinct A and B tiles for its L2).
+__device__ __forceinline__ void tile_of(int logical, int tiles_m, int tiles_n, int &tile_m, int &tile_n) {
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n, g = logical / per_group, idx = logical - g * per_group;
+  const int rows = min(GM, tiles_m - g * GM);
+  tile_n = idx / rows;
+  tile_m = g * GM + (idx - tile_n * rows);
+}
+
 __device__ __forceinline__ int lds_off(int row, int chunk) {   // element offset of a 16-byte chunk
   return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
@@ -43,15 +53,16 @@ constexpr int EPI_PARTIAL_F32 = 3;
 template <int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                    void *__restrict__ Cv, int M, int N, int K, int tiles_m,
-                                                   int tiles_n) {
+                                                   int tiles_n, int tile_n0) {
   // One array per operand and stage: the compiler orders LDS reads against in-flight direct-to-LDS
   // loads by object, so separate objects let the reads of one stage overlap the loads into the other.
   __shared__ __attribute__((aligned(16))) bf16 As0[LDS_TILE], As1[LDS_TILE], Bs0[LDS_TILE], Bs1[LDS_TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int logical = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int tile_n = logical / tiles_m, tile_m = logical - tile_n * tiles_m;
+  int tile_m, tile_n;
+  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  tile_n += tile_n0;                 // this launch covers n-tiles [tile_n0, tile_n0 + tiles_n)
   const int m0 = tile_m * BM;
 
   // Global source of this thread's four 16-byte chunks per operand.  Tiles are brought in by
@@ -189,120 +200,175 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
 // ---------------------------------------------------------------------------------------------
 // Large-tile variant for launches that fill the chip with 256x256 tiles.  Global->LDS traffic
 // per flop halves against the 128x128 tile (a CU's vector-memory path moves ~50-60 bytes/clock,
-// which caps the small tile at about half the MFMA rate), and each LDS fragment read feeds more
-// MFMAs: 8 waves, wave tile 128x64 (4x2 MFMA tiles: 6 fragment reads per 8 MFMAs).  128 KB of
-// LDS (two stages of A and B), one workgroup per CU, two waves per SIMD.
-constexpr int LM = 256, LN = 256;
-constexpr int L_TILE = LM * BK;          // elements per operand tile
+// which caps the small tile at about half the MFMA rate), and a fragment read (1 KB per wave)
+// serves more MFMAs: 4 waves, one per SIMD, each own 128x128 of the tile as 4x4 MFMA tiles (8
+// fragment reads per 16 MFMAs), the 256 accumulator registers in the AGPR half of the wave's 512.
+//
+// With one wave per SIMD nothing else covers a stall, so every kind of instruction is spread
+// evenly through the MFMA stream.  K is walked in steps of 32 through four LDS stages (128 KB):
+// while step k is multiplied out of stage k%4, the loads of step k+3 stream into the stage that
+// step k-1 has just left, one load per four MFMAs, so the vector-memory path never sees a burst
+// and a load has three steps to land.  Per step there are two sub-steps of 16 MFMAs; the fragments
+// of the next sub-step are read between the MFMAs of the current one.  The barrier of a step sits
+// before its second sub-step: past it every wave is done reading the previous stage and the next
+// stage has landed.  LDS rows are 64 bytes here, so the 16-byte chunks are swizzled by row/4.
+constexpr int LM = 256, LN = 256, LK = 32;
+constexpr int L_TILE = LM * LK;          // elements per operand and stage
+
+__device__ __forceinline__ int lds_off32(int row, int chunk) {
+  return row * LK + ((chunk ^ ((row >> 2) & 3)) << 3);
+}
 
 template <int EPI>
-__global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
+__global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                          void *__restrict__ Cv, int M, int N, int K, int tiles_m,
                                                          int tiles_n) {
-  __shared__ __attribute__((aligned(16))) bf16 As0[L_TILE], As1[L_TILE], Bs0[L_TILE], Bs1[L_TILE];   // 128 KB
+  // one array per operand and stage (the compiler orders LDS reads against in-flight loads by object)
+  __shared__ __attribute__((aligned(16))) bf16 As0[L_TILE], As1[L_TILE], As2[L_TILE], As3[L_TILE];
+  __shared__ __attribute__((aligned(16))) bf16 Bs0[L_TILE], Bs1[L_TILE], Bs2[L_TILE], Bs3[L_TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
-  const int logical = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int tile_n = logical / tiles_m, tile_m = logical - tile_n * tiles_m;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * LM;
 
-  const bf16 *a_src[4], *b_src[4];
+  // This thread's four 16-byte chunks per operand and step: tile rows tid/4 + 64 i, and the same
+  // chunk for every i (the swizzle term (row/4)%4 does not depend on i).  One wave-wide load fills
+  // 1 KB of LDS in lane order, i.e. 16 rows of 4 chunk slots.
+  const int row0 = tid >> 2, chunk = (tid & 3) ^ ((row0 >> 2) & 3);
+  const bf16 *a_src[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int c = tid + 512 * i, row = c >> 3, chunk = (c & 7) ^ ((row >> 1) & 7);   // swizzle on the global side
-    int am = m0 + row;
-    am = am < M ? am : M - 1;
+    int am = m0 + row0 + 64 * i;
+    am = am < M ? am : M - 1;                       // tail rows re-read the last row; never stored
     a_src[i] = A + (size_t)am * K + chunk * 8;
-    int bn;
-    if (EPI == ARB_EPI_SWIGLU_BF16) {
-      // tile-local row r: wave column r/64, MFMA tile (r%64)/32 (0 = gate, 1 = up), feature offset r%32
-      const int f = tile_n * 128 + (row >> 6) * 32 + (row & 31);
-      bn = ((row >> 5) & 1) ? N + f : f;            // N = F here
-    } else {
-      bn = tile_n * LN + row;
-    }
-    b_src[i] = B + (size_t)bn * K + chunk * 8;
   }
+  // B rows of chunk i are b_row0 + i * b_rows_per_i.  For SwiGLU the tile-local row r maps to wave column
+  // r/128, MFMA tile (r%128)/32 (even = gate, odd = up) and feature offset r%32, i.e. feature
+  // tile_n*128 + (r/64)*32 + r%32 of the gate (r/32 even) or up (odd) half; N = F there.
+  const int b_row0 = EPI == ARB_EPI_SWIGLU_BF16 ? tile_n * 128 + (row0 & 31) + ((row0 >> 5) & 1) * N : tile_n * LN + row0;
+  const size_t b_step = (size_t)(EPI == ARB_EPI_SWIGLU_BF16 ? 32 : 64) * K;
+  const bf16 *b_src = B + (size_t)b_row0 * K + chunk * 8;
 
-  f32x16 acc[4][2];
+  f32x16 acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = K / BK, last = nk - 1;
+  const int nk = K / LK, last = nk - 1;
   const int frag_row = lane & 31, frag_half = lane >> 5;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  auto dma = [&](int buf, int kt) {
+#define ARB_STAGE(base, s) ((s) == 0 ? base##0 : (s) == 1 ? base##1 : (s) == 2 ? base##2 : base##3)
+  auto dma_a = [&](int s, int kt) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int slot = (i * 8 + wave_u) * 512;
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * BK), LDS_PTR((buf ? As1 : As0) + slot), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src[i] + (size_t)kt * BK), LDS_PTR((buf ? Bs1 : Bs0) + slot), 16, 0, 0);
-    }
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * LK), LDS_PTR(ARB_STAGE(As, s) + (i * 4 + wave_u) * 512), 16, 0, 0);
   };
-  auto compute = [&](int buf) {
-    bf16x8 fa[2][4], fb[2][2];
-    auto frags = [&](int slot, int kk) {
+  auto dma_b = [&](int s, int kt) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        fa[slot][i] = *(const bf16x8 *)&(buf ? As1 : As0)[lds_off(wm * 128 + i * 32 + frag_row, kk * 2 + frag_half)];
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        fb[slot][j] = *(const bf16x8 *)&(buf ? Bs1 : Bs0)[lds_off(wn * 64 + j * 32 + frag_row, kk * 2 + frag_half)];
-    };
-    frags(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) frags((kk + 1) & 1, kk + 1);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src + i * b_step + (size_t)kt * LK), LDS_PTR(ARB_STAGE(Bs, s) + (i * 4 + wave_u) * 512), 16, 0, 0);
   };
-
-  // The loads of step kt+1 stream into the other LDS stage while step kt is multiplied out
-  // (branch-free body, see the small-tile kernel).
-  dma(0, 0);
-  __syncthreads();
-  int kt = 0;
-  for (; kt + 2 <= nk; kt += 2) {
-    dma(1, kt + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(0);
-    __syncthreads();
-    dma(0, min(kt + 2, last));
-    __builtin_amdgcn_sched_barrier(0);
-    compute(1);
-    __syncthreads();
-  }
-  if (kt < nk) compute(0);
-
-  if (EPI == ARB_EPI_SWIGLU_BF16) {
-    bf16 *C = (bf16 *)Cv;
-    const int col = tile_n * 128 + wn * 32 + frag_row;
+  bf16x8 fa[2][4], fb[2][4];
+  // Fragment reads in the order the MFMAs (row-major over the 4x4 tiles) first need them.
+  // The swizzle term of a fragment row depends on frag_row only, so each operand needs one LDS
+  // offset per sub-step; MFMA tile and stage are constant displacements from it.
+  const int a_off[2] = {lds_off32(wm * 128 + frag_row, frag_half), lds_off32(wm * 128 + frag_row, 2 + frag_half)};
+  const int b_off[2] = {lds_off32(wn * 128 + frag_row, frag_half), lds_off32(wn * 128 + frag_row, 2 + frag_half)};
+  auto frags = [&](int slot, int s, int kk) {
+    auto rd_a = [&](int i) { fa[slot][i] = *(const bf16x8 *)&ARB_STAGE(As, s)[a_off[kk] + i * 32 * LK]; };
+    auto rd_b = [&](int j) { fb[slot][j] = *(const bf16x8 *)&ARB_STAGE(Bs, s)[b_off[kk] + j * 32 * LK]; };
+    rd_a(0); rd_b(0); rd_b(1); rd_b(2); rd_b(3); rd_a(1); rd_a(2); rd_a(3);
+  };
+  auto mfmas = [&](int slot) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-        if (m < M) {
-          const float gte = acc[i][0][r], up = acc[i][1][r];
-          C[(size_t)m * N + col] = (bf16)(gte / (1.0f + __expf(-gte)) * up);
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+  };
+  // 16 MFMAs with at most one other memory instruction between two of them: 8 fragment reads and 4
+  // global->LDS loads behind the first twelve, so the reads have returned by the end of the sub-step
+  auto spread = [&]() {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // 1 global->LDS load
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // Step out of stage s; on entry fragment slot 0 holds its first sub-step.  `refill` is the step
+  // loaded into the stage before s (clamped to the last step past the end; those copies are never read).
+  auto step = [&](int s, int refill) {
+    const int prev = (s + 3) & 3, next = (s + 1) & 3;
+    frags(1, s, 1);
+    dma_a(prev, refill);
+    mfmas(0);
+    spread();
+    // Hand-over of the stages.  Before the barrier this wave's reads of stage s have returned
+    // (lgkmcnt 0) and its loads of the next step have landed: those are the oldest 8 of its loads in
+    // flight, the 12 issued since may stay in flight (vmcnt 12).  A full workgroup fence would wait
+    // for all of them.
+    __builtin_amdgcn_s_waitcnt(0x007C);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    frags(0, next, 0);
+    dma_b(prev, refill);
+    mfmas(1);
+    spread();
+  };
+
+  dma_a(0, 0); dma_b(0, 0);
+  dma_a(1, min(1, last)); dma_b(1, min(1, last));
+  dma_a(2, min(2, last)); dma_b(2, min(2, last));
+  __builtin_amdgcn_s_waitcnt(0x0070);       // vmcnt(0) lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  frags(0, 0, 0);
+  int kt = 0;
+  for (; kt + 4 <= nk; kt += 4) {
+    step(0, min(kt + 3, last));
+    step(1, min(kt + 4, last));
+    step(2, min(kt + 5, last));
+    step(3, min(kt + 6, last));
+  }
+  if (kt < nk) {                              // K is a multiple of 64, so two steps are left
+    step(0, last);
+    step(1, last);
+  }
+#undef ARB_STAGE
+
+  if (EPI == ARB_EPI_SWIGLU_BF16) {
+    bf16 *C = (bf16 *)Cv;
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp) {
+      const int col = tile_n * 128 + wn * 64 + jp * 32 + frag_row;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+          if (m < M) {
+            const float gte = acc[i][2 * jp][r], up = acc[i][2 * jp + 1][r];
+            C[(size_t)m * N + col] = (bf16)(gte / (1.0f + __expf(-gte)) * up);
+          }
         }
-      }
+    }
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = tile_n * LN + wn * 64 + j * 32 + frag_row;
+      for (int j = 0; j < 4; ++j) {
+        const int col = tile_n * LN + wn * 128 + j * 32 + frag_row;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
@@ -320,8 +386,6 @@ __global__ __launch_bounds__(512, 1) void gemm256_kernel(const bf16 *__restrict_
 }
 
 }  // namespace
-
-static const int kBigTileMinTiles = 200;
 
 int gemm_residual_splits(int M, int N, int K) {
   // enough workgroups to fill 256 CUs, each keeping at least 4 K-steps; the partials cost
@@ -349,13 +413,20 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   }
   if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32) return arb_fail(ARB_EINVAL, "gemm: split-K needs the residual epilogue");
   if (splits < 1 || splits > K / BK) return arb_fail(ARB_EINVAL, "gemm: %d splits of %d K-steps", splits, K / BK);
-  // Large tiles (one per CU at a time) when whole rounds of 256 of them are at least 80 % full
-  const int big_n = epilogue == ARB_EPI_SWIGLU_BF16 ? 128 : LN;
-  const int big_tiles = N % big_n == 0 ? ceil_div(M, LM) * (N / big_n) : 0;
-  if (splits == 1 && big_tiles >= kBigTileMinTiles && 5 * big_tiles >= 4 * 256 * ceil_div(big_tiles, 256)) {
-    const int tm = ceil_div(M, LM), tn = N / big_n;
-    const dim3 bgrid(tm * tn), bblock(512);
-#define ARB_BIG(E) hipLaunchKernelGGL((gemm256_kernel<E>), bgrid, bblock, 0, st, A, B, C, M, N, K, tm, tn)
+  // Large tiles run one per CU, so they go in whole rounds of 256: as many n-tile columns as fill whole
+  // rounds (all of them when the last round would be at least 80 % full), the remaining columns in
+  // 128x128 tiles.  With less than one round of large tiles everything runs in small ones.
+  const int big_n = epilogue == ARB_EPI_SWIGLU_BF16 ? 128 : LN;       // a large n-tile is two small ones
+  int big_cols = 0;                                   // n-tile columns given to the large-tile kernel
+  if (splits == 1 && N % big_n == 0) {
+    const int tm = ceil_div(M, LM), tn = N / big_n, total = tm * tn, tail = total % 256;
+    big_cols = 5 * tail >= 4 * 256 || tail == 0 ? tn : (total - tail) / tm;
+    if (total < 205) big_cols = 0;
+  }
+  if (big_cols > 0) {
+    const int tm = ceil_div(M, LM);
+    const dim3 bgrid(tm * big_cols), bblock(256);
+#define ARB_BIG(E) hipLaunchKernelGGL((gemm256_kernel<E>), bgrid, bblock, 0, st, A, B, C, M, N, K, tm, big_cols)
     switch (epilogue) {
       case ARB_EPI_STORE_BF16: ARB_BIG(ARB_EPI_STORE_BF16); break;
       case ARB_EPI_RESIDUAL_F32: ARB_BIG(ARB_EPI_RESIDUAL_F32); break;
@@ -364,25 +435,21 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
     }
 #undef ARB_BIG
     ARB_CHECK_LAUNCH("gemm256");
-    return ARB_OK;
   }
+  const int tile_n0 = big_cols * 2;                   // small n-tiles covered by the large-tile launch
+  tiles_n -= tile_n0;
+  if (tiles_n == 0) return ARB_OK;
   const dim3 grid(tiles_m * tiles_n, splits), block(256);
+#define ARB_SMALL(E) hipLaunchKernelGGL((gemm_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0)
   switch (epilogue) {
-    case ARB_EPI_STORE_BF16:
-      hipLaunchKernelGGL((gemm_kernel<ARB_EPI_STORE_BF16>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
-      break;
+    case ARB_EPI_STORE_BF16: ARB_SMALL(ARB_EPI_STORE_BF16); break;
     case ARB_EPI_RESIDUAL_F32:
-      if (splits > 1)
-        hipLaunchKernelGGL((gemm_kernel<EPI_PARTIAL_F32>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
-      else
-        hipLaunchKernelGGL((gemm_kernel<ARB_EPI_RESIDUAL_F32>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
+      if (splits > 1) ARB_SMALL(EPI_PARTIAL_F32); else ARB_SMALL(ARB_EPI_RESIDUAL_F32);
       break;
-    case ARB_EPI_SWIGLU_BF16:
-      hipLaunchKernelGGL((gemm_kernel<ARB_EPI_SWIGLU_BF16>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n);
-      break;
-    default:
-      return arb_fail(ARB_EINVAL, "gemm: unknown epilogue %d", epilogue);
+    case ARB_EPI_SWIGLU_BF16: ARB_SMALL(ARB_EPI_SWIGLU_BF16); break;
+    default: return arb_fail(ARB_EINVAL, "gemm: unknown epilogue %d", epilogue);
   }
+#undef ARB_SMALL
   ARB_CHECK_LAUNCH("gemm");
   return ARB_OK;
 }

@@ -59,7 +59,8 @@ def test_slot_mapping_bit_exact(A, name):
 # --------------------------------------------------------------------------- GEMM
 
 @pytest.mark.parametrize("M,N,K", [(1, 128, 64), (200, 256, 192), (1024, 2048, 1536), (333, 1536, 8960),
-                                   (3300, 4096, 256)])   # the last one takes the 256x256-tile kernel
+                                   (3300, 4096, 256),    # 256x256-tile kernel alone (208 tiles)
+                                   (4000, 4864, 320)])   # 256x256 tiles for 16 n-columns, 128x128 tiles for the other 6
 def test_gemm_store_and_residual(A, M, N, K):
     a, b = rand_bf16((M, K), 1.0, 11), rand_bf16((N, K), 0.02, 12)
     ref = bf16_np(a) @ bf16_np(b).T
@@ -71,7 +72,9 @@ def test_gemm_store_and_residual(A, M, N, K):
     assert rel_err(h.cpu().numpy(), h0.cpu().numpy().astype(np.float64) + ref) < 1e-5
 
 
-@pytest.mark.parametrize("M,F,K", [(130, 64, 128), (1024, 8960, 1536), (1000, 8960, 192)])
+@pytest.mark.parametrize("M,F,K", [(130, 64, 128), (1024, 8960, 1536), (1000, 8960, 192),
+                                   (3300, 2048, 128),    # 256x256-tile kernel alone (208 tiles)
+                                   (2000, 4736, 192)])   # large tiles for 32 n-columns, small ones for the rest
 def test_gemm_swiglu(A, M, F, K):
     a, b = rand_bf16((M, K), 1.0, 13), rand_bf16((2 * F, K), 0.05, 14)
     af, bf = bf16_np(a), bf16_np(b)
