@@ -6,6 +6,7 @@ one batch of the 1.5B-router-shaped workload (16 sequences, 2048-token cached
 prefix, 64-token drafted step), inputs resident in HBM.  Prints one JSON line.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -18,6 +19,10 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# Counter runs of the dominant kernel on workload C2 (profiles/score_steps_C2_hbm_traffic.txt): scaled
+# FETCH_SIZE + WRITE_SIZE bytes per launch, and the SHA-256 of the csrc/gemm.hip they were taken with.
+COUNTED_GATE_UP_BYTES = 75980627 + 20828123
+COUNTED_GEMM_SHA256 = "43c2bcd287d8d40e0256f3715bd271bdd7d64d8fd6de7891fb5db8f655235b49"
 
 
 def cpu_baseline(w, sess, layers: int):
@@ -61,6 +66,9 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--cpu-layers", type=int, default=-1, help="layers of the oracle sample (-1 = all, 0 = skip the CPU baseline)")
     ap.add_argument("--breakdown", action="store_true", help="also time each stage (extra passes, not in the timed region)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="before the warm-up, run one plain device copy of this many MiB (a kernel of known traffic "
+                         "that hardware-counter runs are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (sequences are independent; see DESIGN.md for how the path "
@@ -87,11 +95,24 @@ def main():
         A.arb_score_steps(model, sess.kv, sess.dbatch, batch.tau, ws=sess.ws, scores=scores, escalate=esc,
                           hidden=hidden)
 
+    if args.copy_probe_mib > 0:
+        src = torch.arange(args.copy_probe_mib << 18, dtype=torch.float32, device="cuda")   # 4 bytes each
+        torch.empty_like(src).copy_(src)
+        del src
     for _ in range(args.warmup):
         step()
-    # the dominant kernel (gate/up projection with the SwiGLU epilogue) is bracketed by HIP
-    # events inside the library, on the stream it runs on, during the timed steps
-    timer = A.StageTimer(model, A.ARB_STAGE_GATE_UP, args.steps * L)
+    # The dominant kernel is bracketed by HIP events inside the library, on the stream it runs on,
+    # during the timed steps: the gate/up projection with the SwiGLU epilogue, or, where that
+    # projection is launched as two kernels, the 256x256-tile kernel that does most of its columns.
+    F, d = w.model.d_ffn, w.model.d_model
+    large_cols = A.arb_gemm_large_tile_columns(T, F, d, A.ARB_EPI_SWIGLU_BF16)
+    if large_cols > 0:
+        gu_stage, gu_features = A.ARB_STAGE_GATE_UP_LARGE, large_cols * 128
+        gu_kernel = f"gemm256_kernel<SWIGLU> (gate/up projection, features [0, {gu_features}) of {F} in 256x256 tiles)"
+    else:
+        gu_stage, gu_features = A.ARB_STAGE_GATE_UP, F
+        gu_kernel = "gemm_kernel<SWIGLU> (gate/up projection, 128x128 tiles)"
+    timer = A.StageTimer(model, gu_stage, args.steps * L)
     timer.arm()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -104,8 +125,14 @@ def main():
     timer.close()
     ms_per_step = dt / args.steps * 1e3
     gu_avg_ms = sum(gu_ms) / len(gu_ms)
-    gu_flops = 2.0 * T * (2 * w.model.d_ffn) * w.model.d_model           # per launch
+    gu_flops = 2.0 * T * (2 * gu_features) * d                            # per launch of that kernel
     achieved = gu_flops / (gu_avg_ms * 1e-3) / 1e12
+    # HBM-side bytes per launch of that kernel from the FETCH_SIZE / WRITE_SIZE counter runs
+    # (profiles/score_steps_C2_hbm_traffic.txt); only valid for the kernel source they were taken with
+    traffic = None
+    with open(os.path.join(os.path.dirname(os.path.abspath(A.__file__)), "csrc", "gemm.hip"), "rb") as f:
+        if args.workload == "C2" and hashlib.sha256(f.read()).hexdigest() == COUNTED_GEMM_SHA256:
+            traffic = COUNTED_GATE_UP_BYTES
 
     out = {
         "metric": "scored step-tokens/sec on 1 MI355X", "value": T / (ms_per_step * 1e-3), "unit": "scored step-tokens/s",
@@ -113,8 +140,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "layers": L, "d_model": w.model.d_model, "batch": batch.batch,
                    "prefix_tokens": int(batch.prefix_lens.sum()), "step_tokens": T, "kv": f"paged-16 {w.tables}"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<SWIGLU> (gate/up projection)", "achieved": achieved,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+        "roofline": {"bound": "mfma", "kernel": gu_kernel, "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "avg_launch_ms": gu_avg_ms, "launches": n, "flops_per_launch": gu_flops},
     }
 
@@ -141,7 +168,7 @@ def main():
                             "hbm_frac": (kv_bytes + qo_bytes) / (bd["attention"] / L * 1e-3) / 1e9 / PEAK_HBM_GBS,
                             "TFLOPs": attn_flops / (bd["attention"] / L * 1e-3) / 1e12}
         gemm_flops = {"qkv": 2.0 * T * m.qkv_rows * m.d_model, "oproj": 2.0 * T * m.d_model * m.n_q_heads * m.head_dim,
-                      "gate_up": gu_flops, "down": 2.0 * T * m.d_model * m.d_ffn}
+                      "gate_up": 2.0 * T * 2 * m.d_ffn * m.d_model, "down": 2.0 * T * m.d_model * m.d_ffn}
         out["gemm_TFLOPs"] = {k: v / (bd[k] / L * 1e-3) / 1e12 for k, v in gemm_flops.items()}
 
     if args.cpu_layers < 0:

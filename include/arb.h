@@ -169,6 +169,11 @@ typedef enum {
 arb_status arb_stage_gemm(const void *A, const void *B, void *C, int32_t M, int32_t N, int32_t K, int32_t epilogue,
                           void *stream);
 
+/* How the projection GEMM of that shape is launched (host arithmetic only): the number of leading
+ * 256-column blocks of C (128-feature blocks for SWIGLU) that one kernel computes in 256x256 tiles; the
+ * remaining columns go to a second kernel in 128x128 tiles.  0 = one kernel, 128x128 tiles throughout. */
+int32_t arb_gemm_large_tile_columns(int32_t M, int32_t N, int32_t K, int32_t epilogue);
+
 /* Append-attention of one layer.  q: device bf16, row t at q + t*q_row_stride elements, heads contiguous
  * [Hq, hd], already rotated; the pools already hold the step's keys/values.  out: bf16 [T, Hq*hd]. */
 arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, const void *k_pool,
@@ -208,7 +213,9 @@ arb_status arb_stage_layers(arb_model *m, const arb_kv *kv, const arb_batch *bat
  * number of launches recorded since arming.  n == 0 disarms. */
 typedef enum {
   ARB_STAGE_QKV = 0, ARB_STAGE_ATTENTION = 1, ARB_STAGE_OPROJ = 2, ARB_STAGE_GATE_UP = 3, ARB_STAGE_DOWN = 4,
-  ARB_STAGE_NORM = 5, ARB_STAGE_ROPE_APPEND = 6
+  ARB_STAGE_NORM = 5, ARB_STAGE_ROPE_APPEND = 6,
+  ARB_STAGE_GATE_UP_LARGE = 7 /* the 256x256-tile kernel of the gate/up projection alone (an empty interval
+                                 when arb_gemm_large_tile_columns is 0) */
 } arb_trace_stage;
 arb_status arb_model_trace(arb_model *m, int32_t stage, void *const *start, void *const *stop, int32_t n);
 int32_t arb_model_trace_count(const arb_model *m);

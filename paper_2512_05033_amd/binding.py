@@ -21,12 +21,12 @@ ARB_POOL_MEAN, ARB_POOL_LAST = 0, 1
 ARB_ESCALATE_IF_GT, ARB_ACCEPT_IF_GT = 0, 1
 ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16 = 0, 1, 2
 (ARB_STAGE_QKV, ARB_STAGE_ATTENTION, ARB_STAGE_OPROJ, ARB_STAGE_GATE_UP, ARB_STAGE_DOWN, ARB_STAGE_NORM,
- ARB_STAGE_ROPE_APPEND) = range(7)
+ ARB_STAGE_ROPE_APPEND, ARB_STAGE_GATE_UP_LARGE) = range(8)
 _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4: "ARB_EHIP", 5: "ARB_EUNSUPPORTED"}
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
            "arb_route", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
-           "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_model_trace", "arb_model_trace_count",
+           "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
 
@@ -95,8 +95,10 @@ def load_library(path: Optional[str] = None):
     lib.arb_model_trace.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32]
     lib.arb_model_trace_count.argtypes = [C.c_void_p]
     lib.arb_model_trace_count.restype = C.c_int32
+    lib.arb_gemm_large_tile_columns.argtypes = [C.c_int32] * 4
+    lib.arb_gemm_large_tile_columns.restype = C.c_int32
     for name in EXPORTS:
-        if name not in ("arb_last_error", "arb_workspace_bytes", "arb_model_trace_count"):
+        if name not in ("arb_last_error", "arb_workspace_bytes", "arb_model_trace_count", "arb_gemm_large_tile_columns"):
             getattr(lib, name).restype = C.c_int
     if path == _LIB_PATH:
         _lib = lib
@@ -261,6 +263,10 @@ def arb_stage_gemm(a: torch.Tensor, b: torch.Tensor, epilogue: int = ARB_EPI_STO
         raise ValueError("output shape")
     _check(load_library().arb_stage_gemm(_ptr(a), _ptr(b), _ptr(out), M, N, K, epilogue, _stream(stream)))
     return out
+
+
+def arb_gemm_large_tile_columns(M: int, N: int, K: int, epilogue: int) -> int:
+    return int(load_library().arb_gemm_large_tile_columns(M, N, K, epilogue))
 
 
 def arb_stage_attention(model: Model, q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,

@@ -275,7 +275,11 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     pending = 0;
     {
       TraceScope t(m, ARB_STAGE_GATE_UP, st);
-      s = launch_gemm(w.x, m->wgu[l], w.act, T, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, st);
+      {
+        TraceScope large(m, ARB_STAGE_GATE_UP_LARGE, st);
+        s = launch_gemm(w.x, m->wgu[l], w.act, T, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, st, 1, GEMM_PART_LARGE);
+      }
+      if (!s) s = launch_gemm(w.x, m->wgu[l], w.act, T, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, st, 1, GEMM_PART_SMALL);
     }
     if (s) return s;
     {
@@ -340,6 +344,10 @@ extern "C" arb_status arb_stage_gemm(const void *A, const void *B, void *C, int3
   if (M == 0) return ARB_OK;
   if (!A || !B || !C) return arb_fail(ARB_EINVAL, "arb_stage_gemm: null pointer");
   return launch_gemm((const bf16 *)A, (const bf16 *)B, C, M, N, K, epilogue, (hipStream_t)stream);
+}
+
+extern "C" int32_t arb_gemm_large_tile_columns(int32_t M, int32_t N, int32_t K, int32_t epilogue) {
+  return gemm_large_cols(M, N, K, epilogue, 1);
 }
 
 extern "C" arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, const void *k_pool,

@@ -43,8 +43,12 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // gemm.hip
 // With splits > 1 (residual epilogue only) C is not accumulated into: split s writes its fp32 partial
 // product to C + s*M*N and the consumer adds the partials to the residual stream (see the norm kernels).
+// A launch is up to two kernels: n-tile columns [0, gemm_large_cols) in 256x256 tiles, the rest in
+// 128x128 tiles; `part` restricts the call to one of them.
+enum { GEMM_PART_ALL = 0, GEMM_PART_LARGE = 1, GEMM_PART_SMALL = 2 };
 arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st,
-                       int splits = 1);
+                       int splits = 1, int part = GEMM_PART_ALL);
+int gemm_large_cols(int M, int N, int K, int epilogue, int splits);   // in units of 256 columns (128 SwiGLU features)
 int gemm_residual_splits(int M, int N, int K);
 
 // attention.hip

@@ -397,8 +397,20 @@ int gemm_residual_splits(int M, int N, int K) {
   return s < 1 ? 1 : s;
 }
 
+int gemm_large_cols(int M, int N, int K, int epilogue, int splits) {
+  // Large tiles run one per CU, so they go in whole rounds of 256: as many n-tile columns as fill whole
+  // rounds (all of them when the last round would be at least 80 % full), the remaining columns in
+  // 128x128 tiles.  With less than one round of large tiles everything runs in small ones.
+  (void)K;
+  const int big_n = epilogue == ARB_EPI_SWIGLU_BF16 ? 128 : LN;       // a large n-tile is two small ones
+  if (splits != 1 || M <= 0 || N <= 0 || N % big_n != 0) return 0;
+  const int tm = ceil_div(M, LM), tn = N / big_n, total = tm * tn, tail = total % 256;
+  if (total < 205) return 0;
+  return 5 * tail >= 4 * 256 || tail == 0 ? tn : (total - tail) / tm;
+}
+
 arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st,
-                       int splits) {
+                       int splits, int part) {
   if (M == 0) return ARB_OK;
   if (M < 0 || N <= 0 || K <= 0) return arb_fail(ARB_EINVAL, "gemm: M=%d N=%d K=%d", M, N, K);
   if (K % BK != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm: K=%d is not a multiple of %d", K, BK);
@@ -413,17 +425,8 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   }
   if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32) return arb_fail(ARB_EINVAL, "gemm: split-K needs the residual epilogue");
   if (splits < 1 || splits > K / BK) return arb_fail(ARB_EINVAL, "gemm: %d splits of %d K-steps", splits, K / BK);
-  // Large tiles run one per CU, so they go in whole rounds of 256: as many n-tile columns as fill whole
-  // rounds (all of them when the last round would be at least 80 % full), the remaining columns in
-  // 128x128 tiles.  With less than one round of large tiles everything runs in small ones.
-  const int big_n = epilogue == ARB_EPI_SWIGLU_BF16 ? 128 : LN;       // a large n-tile is two small ones
-  int big_cols = 0;                                   // n-tile columns given to the large-tile kernel
-  if (splits == 1 && N % big_n == 0) {
-    const int tm = ceil_div(M, LM), tn = N / big_n, total = tm * tn, tail = total % 256;
-    big_cols = 5 * tail >= 4 * 256 || tail == 0 ? tn : (total - tail) / tm;
-    if (total < 205) big_cols = 0;
-  }
-  if (big_cols > 0) {
+  const int big_cols = gemm_large_cols(M, N, K, epilogue, splits);   // n-tile columns given to the large-tile kernel
+  if (big_cols > 0 && part != GEMM_PART_SMALL) {
     const int tm = ceil_div(M, LM);
     const dim3 bgrid(tm * big_cols), bblock(256);
 #define ARB_BIG(E) hipLaunchKernelGGL((gemm256_kernel<E>), bgrid, bblock, 0, st, A, B, C, M, N, K, tm, big_cols)
@@ -438,7 +441,7 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   }
   const int tile_n0 = big_cols * 2;                   // small n-tiles covered by the large-tile launch
   tiles_n -= tile_n0;
-  if (tiles_n == 0) return ARB_OK;
+  if (tiles_n == 0 || part == GEMM_PART_LARGE) return ARB_OK;
   const dim3 grid(tiles_m * tiles_n, splits), block(256);
 #define ARB_SMALL(E) hipLaunchKernelGGL((gemm_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0)
   switch (epilogue) {
