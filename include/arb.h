@@ -151,6 +151,22 @@ arb_status arb_prefill(arb_model *m, const arb_kv *kv, const arb_batch *batch, v
  * scores: device fp32 [n]; escalate: device uint8 [n].  n == 0 is a no-op. */
 arb_status arb_route(const float *scores, int32_t n, float tau, int32_t sense, uint8_t *escalate, void *stream);
 
+/* Routing by the true advantage (the ideal policy that Section 4.1 calls the oracle) on two PRM score arrays (Definitions 4.1 and 4.2, Eq. 4.4), all device fp32 [n]:
+ *   delta[i]    = s_t[i] - s_d[i]                      (step-level advantage)
+ *   escalate[i] = 1 iff not (delta[i] <= tau)          (a*_tau; NaN escalates, as in arb_route)
+ *   realized[i] = escalate[i] ? s_t[i] : s_d[i]        (S(a) of Definition 4.2)
+ * Any of the three outputs may be NULL (not all).  If tau_device is not NULL the threshold is read from that
+ * device float (e.g. the output of arb_budget_threshold) and `tau` is ignored.  n == 0 is a no-op. */
+arb_status arb_advantage_route(const float *s_t, const float *s_d, int32_t n, float tau, const float *tau_device,
+                            float *delta, uint8_t *escalate, float *realized, void *stream);
+
+/* The threshold that spends a budget of at most `budget` escalations best (Theorem B.1 and its proof):
+ * *tau_out (device float) = max(0, the (budget+1)-th largest of delta[0..n)), 0 when budget >= n.  With it,
+ * a*_tau escalates the min(budget, #positive) largest positive advantages (fewer if equal values straddle the
+ * cut).  A NaN escalates under any tau, so NaNs rank first; if they alone exceed the budget the result is
+ * +inf.  One workgroup; meant for n = number of reasoning steps. */
+arb_status arb_budget_threshold(const float *delta, int32_t n, int32_t budget, float *tau_out, void *stream);
+
 /* Pool slot of every step token, slot = block_tables[b][pos/kv_block]*kv_block + pos%kv_block with
  * pos = prefix_lens[b] + i, as the forward computes it.  slots: device int32 [total_tokens]. */
 arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream);

@@ -324,3 +324,23 @@ def realized_score(s_d, s_t, a) -> np.ndarray:
     """S(a) = (1-a) s_d + a s_t (Definition 4.2)."""
     a = np.asarray(a, dtype=F)
     return (1.0 - a) * np.asarray(s_d, dtype=F) + a * np.asarray(s_t, dtype=F)
+
+
+def budget_threshold(delta, budget: int) -> float:
+    """A threshold tau for the oracle policy a_i = 1{Delta_i > tau} under at most `budget`
+    escalations (Theorem B.1 and its proof): the optimum escalates the
+    k = min(budget, #{Delta_i > 0}) largest positive advantages, which any tau with
+    Delta_(k) > tau >= Delta_(k+1) selects.  Returned: max(0, Delta_(budget+1)) with
+    Delta_(N+1) = -inf, in the precision of the input.  Entries that are NaN escalate
+    whatever tau is, so they are ranked above every number; if they alone exceed
+    the budget the result is +inf."""
+    d = np.asarray(delta)
+    n = d.size
+    if budget >= n:
+        return 0.0
+    key = np.where(np.isnan(d), np.inf, d)
+    kth = np.sort(key)[::-1][budget]           # the (budget+1)-th largest
+    if np.isnan(d).sum() > budget:
+        return float("inf")
+    return float(max(kth, 0.0))
+

@@ -25,7 +25,7 @@ ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16 = 0, 1, 2
 _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4: "ARB_EHIP", 5: "ARB_EUNSUPPORTED"}
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
-           "arb_route", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
+           "arb_route", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
            "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
@@ -79,6 +79,9 @@ def load_library(path: Optional[str] = None):
     lib.arb_prefill.argtypes = [C.c_void_p, C.POINTER(_KV), C.POINTER(_Batch), C.c_void_p, C.c_void_p, C.c_size_t,
                                 C.c_void_p]
     lib.arb_route.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.arb_advantage_route.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p]
+    lib.arb_budget_threshold.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_slot_mapping.argtypes = [C.POINTER(_Batch), C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p]
@@ -237,6 +240,28 @@ def arb_route(scores: torch.Tensor, tau: float, sense: int = ARB_ESCALATE_IF_GT,
     _dev(scores, torch.float32)
     out = torch.empty(scores.numel(), dtype=torch.uint8, device=scores.device)
     _check(load_library().arb_route(_ptr(scores), scores.numel(), float(tau), sense, _ptr(out), _stream(stream)))
+    return out
+
+
+def arb_advantage_route(s_t: torch.Tensor, s_d: torch.Tensor, tau=0.0, stream=None):
+    """-> (delta fp32 [n], escalate uint8 [n], realized fp32 [n]); tau: a float, or a 1-element device tensor."""
+    _dev(s_t, torch.float32), _dev(s_d, torch.float32)
+    n = s_t.numel()
+    if s_d.numel() != n:
+        raise ValueError("score arrays differ in length")
+    delta, realized = torch.empty_like(s_t), torch.empty_like(s_t)
+    esc = torch.empty(n, dtype=torch.uint8, device=s_t.device)
+    tau_dev = _dev(tau, torch.float32) if isinstance(tau, torch.Tensor) else None
+    _check(load_library().arb_advantage_route(_ptr(s_t), _ptr(s_d), n, 0.0 if tau_dev is not None else float(tau),
+                                           _ptr(tau_dev), _ptr(delta), _ptr(esc), _ptr(realized), _stream(stream)))
+    return delta, esc, realized
+
+
+def arb_budget_threshold(delta: torch.Tensor, budget: int, stream=None) -> torch.Tensor:
+    """-> 1-element device tensor holding tau (Theorem B.1)."""
+    _dev(delta, torch.float32)
+    out = torch.empty(1, dtype=torch.float32, device=delta.device)
+    _check(load_library().arb_budget_threshold(_ptr(delta), delta.numel(), int(budget), _ptr(out), _stream(stream)))
     return out
 
 

@@ -326,6 +326,23 @@ extern "C" arb_status arb_route(const float *scores, int32_t n, float tau, int32
   return launch_route(scores, n, tau, sense, escalate, (hipStream_t)stream);
 }
 
+extern "C" arb_status arb_advantage_route(const float *s_t, const float *s_d, int32_t n, float tau,
+                                       const float *tau_device, float *delta, uint8_t *escalate, float *realized,
+                                       void *stream) {
+  if (n < 0) return arb_fail(ARB_EINVAL, "arb_advantage_route: n = %d", n);
+  if (n == 0) return ARB_OK;
+  if (!s_t || !s_d) return arb_fail(ARB_EINVAL, "arb_advantage_route: null score array");
+  if (!delta && !escalate && !realized) return arb_fail(ARB_EINVAL, "arb_advantage_route: no output requested");
+  return launch_advantage_route(s_t, s_d, n, tau, tau_device, delta, escalate, realized, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_budget_threshold(const float *delta, int32_t n, int32_t budget, float *tau_out,
+                                           void *stream) {
+  if (n < 0 || budget < 0) return arb_fail(ARB_EINVAL, "arb_budget_threshold: n = %d, budget = %d", n, budget);
+  if (!tau_out || (n > 0 && !delta)) return arb_fail(ARB_EINVAL, "arb_budget_threshold: null pointer");
+  return launch_budget_threshold(delta, n, budget, tau_out, (hipStream_t)stream);
+}
+
 extern "C" arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream) {
   BatchInfo info;
   if (kv_block <= 0) return arb_fail(ARB_EINVAL, "arb_slot_mapping: kv_block %d", kv_block);

@@ -84,3 +84,6 @@ arb_status launch_final_norm_head(const float *h, const float *parts, int n_part
 arb_status launch_pool_route(const float *tok_dot, const int32_t *cu_step_lens, int batch, float b_head, int pool,
                              float tau, float *scores, uint8_t *escalate, hipStream_t st);
 arb_status launch_route(const float *scores, int n, float tau, int sense, uint8_t *escalate, hipStream_t st);
+arb_status launch_advantage_route(const float *s_t, const float *s_d, int n, float tau, const float *tau_device,
+                               float *delta, uint8_t *escalate, float *realized, hipStream_t st);
+arb_status launch_budget_threshold(const float *delta, int n, int budget, float *tau_out, hipStream_t st);

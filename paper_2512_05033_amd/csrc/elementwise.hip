@@ -300,3 +300,93 @@ arb_status launch_route(const float *scores, int n, float tau, int sense, uint8_
   ARB_CHECK_LAUNCH("route");
   return ARB_OK;
 }
+
+// ------------------------------------------------------------- advantage routing
+
+// Definitions 4.1 and 4.2, Eq. 4.4: delta = s_t - s_d; escalate iff not (delta <= tau), the same
+// comparison as route_kernel; realized score = s_t where escalated, s_d elsewhere.
+__global__ void advantage_route_kernel(const float *__restrict__ s_t, const float *__restrict__ s_d, int n, float tau,
+                                    const float *__restrict__ tau_device, float *__restrict__ delta,
+                                    uint8_t *__restrict__ escalate, float *__restrict__ realized) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float t = tau_device ? *tau_device : tau;
+  const float a = s_t[i], b = s_d[i], d = a - b;
+  const bool esc = !(d <= t);
+  if (delta) delta[i] = d;
+  if (escalate) escalate[i] = esc;
+  if (realized) realized[i] = esc ? a : b;
+}
+
+arb_status launch_advantage_route(const float *s_t, const float *s_d, int n, float tau, const float *tau_device,
+                               float *delta, uint8_t *escalate, float *realized, hipStream_t st) {
+  if (n == 0) return ARB_OK;
+  hipLaunchKernelGGL(advantage_route_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, s_t, s_d, n, tau, tau_device, delta,
+                     escalate, realized);
+  ARB_CHECK_LAUNCH("advantage_route");
+  return ARB_OK;
+}
+
+// Threshold for a budget of escalations (Theorem B.1): tau = max(0, the (budget+1)-th largest delta),
+// found by a most-significant-byte-first radix select in one workgroup (n is a number of reasoning
+// steps, not of tokens).  Keys order floats as unsigned integers; NaN, which escalates under any tau,
+// ranks above every number, and if the selected entry is a NaN the result is +inf.
+__device__ __forceinline__ uint32_t order_key(float x) {
+  if (x != x) return 0xFFFFFFFFu;
+  const uint32_t u = __float_as_uint(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(256) void budget_threshold_kernel(const float *__restrict__ delta, int n, int budget,
+                                                               float *__restrict__ tau_out) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sel_prefix, sel_rank;
+  const int tid = threadIdx.x;
+  if (budget >= n) {                        // nothing is cut off: every positive advantage may escalate
+    if (tid == 0) *tau_out = 0.f;
+    return;
+  }
+  uint32_t prefix = 0, rank = (uint32_t)budget;        // rank from the top among keys matching the prefix
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[tid] = 0;
+    __syncthreads();
+    const uint32_t mask = shift == 24 ? 0u : 0xFFFFFFFFu << (shift + 8);
+    for (int i = tid; i < n; i += 256) {
+      const uint32_t k = order_key(delta[i]);
+      if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t r = rank;
+      int b = 255;
+      for (; b > 0; --b) {
+        if (r < hist[b]) break;
+        r -= hist[b];
+      }
+      sel_prefix = prefix | ((uint32_t)b << shift);
+      sel_rank = r;
+    }
+    __syncthreads();
+    prefix = sel_prefix;
+    rank = sel_rank;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    float t;
+    if (prefix == 0xFFFFFFFFu) {
+      t = __uint_as_float(0x7F800000u);                 // the NaNs alone exceed the budget
+    } else {
+      const uint32_t u = (prefix & 0x80000000u) ? (prefix & 0x7FFFFFFFu) : ~prefix;
+      t = __uint_as_float(u);
+      t = t > 0.f ? t : 0.f;
+    }
+    *tau_out = t;
+  }
+}
+
+arb_status launch_budget_threshold(const float *delta, int n, int budget, float *tau_out, hipStream_t st) {
+  hipLaunchKernelGGL(budget_threshold_kernel, dim3(1), dim3(256), 0, st, delta, n, budget, tau_out);
+  ARB_CHECK_LAUNCH("budget_threshold");
+  return ARB_OK;
+}
+

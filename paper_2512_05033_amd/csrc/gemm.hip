@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
         const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
         if (m < M) {
           const float gte = acc[i][0][r], up = acc[i][1][r];
-          C[(size_t)m * N + col] = (bf16)(gte / (1.0f + __expf(-gte)) * up);
+          C[(size_t)m * N + col] = (bf16)(gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up);
         }
       }
   } else {
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
           const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
           if (m < M) {
             const float gte = acc[i][2 * jp][r], up = acc[i][2 * jp + 1][r];
-            C[(size_t)m * N + col] = (bf16)(gte / (1.0f + __expf(-gte)) * up);
+            C[(size_t)m * N + col] = (bf16)(gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up);
           }
         }
     }
@@ -388,10 +388,11 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
 }  // namespace
 
 int gemm_residual_splits(int M, int N, int K) {
-  // enough workgroups to fill 256 CUs, each keeping at least 4 K-steps; the partials cost
-  // 8 bytes of traffic per element and split, so no more splits than that needs
+  // as many workgroups as are resident at once (two per CU on 256 CUs) without starting a second
+  // round, each keeping at least 4 K-steps; the partials cost 8 bytes of traffic per element and
+  // split, so no more splits than that (measured on the 1.5B shape: 5 beats 4 and 6)
   const int tiles = ceil_div(M, BM) * (N / BN), nk = K / BK;
-  int s = ceil_div(384, tiles);
+  int s = 512 / tiles;
   if (s > nk / 4) s = nk / 4;
   if (s > 8) s = 8;
   return s < 1 ? 1 : s;

@@ -102,6 +102,12 @@ def test_batch_validation_happens_on_the_host(lib):
     assert lib.arb_route(None, -1, 0.0, 0, None, None) == B.ARB_EINVAL
     assert lib.arb_route(None, 0, 0.0, 0, None, None) == B.ARB_OK
     assert lib.arb_route(0x1000, 4, 0.0, 9, 0x1000, None) == B.ARB_EINVAL
+    assert lib.arb_advantage_route(None, None, 0, 0.0, None, None, None, None, None) == B.ARB_OK
+    assert lib.arb_advantage_route(None, 0x1000, 4, 0.0, None, 0x1000, None, None, None) == B.ARB_EINVAL
+    assert lib.arb_advantage_route(0x1000, 0x1000, 4, 0.0, None, None, None, None, None) == B.ARB_EINVAL   # no output
+    assert lib.arb_budget_threshold(0x1000, -1, 0, 0x1000, None) == B.ARB_EINVAL
+    assert lib.arb_budget_threshold(0x1000, 4, 1, None, None) == B.ARB_EINVAL
+    assert lib.arb_stage_layers(None, None, None, 0, 1, None, None, None, 0, None) == B.ARB_EINVAL
     assert lib.arb_stage_gemm(0x1000, 0x1000, 0x1000, 8, 128, 96, 0, None) == B.ARB_EUNSUPPORTED
     assert lib.arb_stage_gemm(0x1000, 0x1000, 0x1000, 8, 100, 128, 0, None) == B.ARB_EUNSUPPORTED
     lib.arb_model_destroy(h)

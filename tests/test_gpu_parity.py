@@ -172,6 +172,43 @@ def test_route_matches_oracle_including_ties_and_nan(A):
     assert A.arb_route(torch.empty(0, device="cuda"), 0.0).numel() == 0
 
 
+def test_advantage_route_and_budget_threshold(A):
+    """Definitions 4.1/4.2, Eq. 4.4 and Theorem B.1 on the device against the oracle: bit-exact
+    (scores on a 2^-10 grid, so that the fp32 difference is exact on both sides)."""
+    r = np.random.default_rng(5)
+    for n in (1, 7, 1000, 100003):
+        s_d = (r.integers(-4096, 4096, n) / 1024.0).astype(np.float32)
+        s_t = (r.integers(-4096, 4096, n) / 1024.0).astype(np.float32)
+        s_t[: n // 5] = s_d[: n // 5]                                  # ties: delta = 0 accepts
+        if n > 5:
+            s_t[5] = np.nan
+        td, tt = torch.from_numpy(s_d).cuda(), torch.from_numpy(s_t).cuda()
+        d_ref = O.advantage(s_t, s_d)
+        for tau in (0.0, -0.25, 1.5):
+            delta, esc, realized = A.arb_advantage_route(tt, td, tau)
+            a_ref = O.route(d_ref, tau)
+            assert np.array_equal(delta.cpu().numpy().astype(np.float64), d_ref, equal_nan=True)
+            assert np.array_equal(esc.cpu().numpy(), a_ref)
+            assert np.array_equal(realized.cpu().numpy().astype(np.float64), O.realized_score(s_d, s_t, a_ref),
+                                  equal_nan=True)
+        d32 = torch.from_numpy(d_ref.astype(np.float32)).cuda()
+        for budget in sorted({0, 1, 2, n // 3, n - 1, n, n + 5}):
+            tau_dev = A.arb_budget_threshold(d32, budget)
+            tau_ref = O.budget_threshold(d_ref.astype(np.float32), budget)
+            assert float(tau_dev.item()) == tau_ref, (n, budget)
+            _, esc, _ = A.arb_advantage_route(tt, td, tau_dev)            # threshold taken from the device
+            assert np.array_equal(esc.cpu().numpy(), O.route(d_ref, tau_ref))
+            assert esc.sum().item() <= max(budget, int(np.isnan(d_ref).sum()))
+    # all advantages negative, all equal, NaNs beyond the budget
+    neg = torch.full((50,), -1.0, device="cuda")
+    assert A.arb_budget_threshold(neg, 10).item() == 0.0
+    same = torch.full((50,), 2.0, device="cuda")
+    assert A.arb_budget_threshold(same, 10).item() == 2.0
+    nans = torch.tensor([1.0, float("nan"), float("nan"), 3.0], device="cuda")
+    assert A.arb_budget_threshold(nans, 1).item() == float("inf") and A.arb_budget_threshold(nans, 2).item() == 3.0
+    assert A.arb_advantage_route(torch.empty(0, device="cuda"), torch.empty(0, device="cuda"))[1].numel() == 0
+
+
 # ---------------------------------------------------------------------- attention
 
 def _attention_case(A, shape, prefix, steps, peaky, seed):

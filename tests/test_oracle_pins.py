@@ -488,6 +488,26 @@ def test_route_zero_waste_corollary_and_realized_score():
     assert np.allclose(O.realized_score(s_d, s_t, a), s_d + a * delta)
 
 
+@pytest.mark.parametrize("n,seed", [(1, 0), (5, 1), (9, 2), (10, 3)])
+def test_budget_threshold_attains_the_brute_force_optimum(n, seed):
+    """Theorem B.1 by exhaustion: for every budget the threshold policy's value equals the
+    maximum of sum a_i*Delta_i over all 2^n policies with at most `budget` escalations."""
+    import itertools
+    delta = np.random.default_rng(seed).normal(0.2, 1, n).astype(np.float32)
+    for budget in range(n + 2):
+        best = max(sum(d for d, a in zip(delta.astype(np.float64), bits) if a)
+                   for bits in itertools.product((0, 1), repeat=n) if sum(bits) <= budget)
+        tau = O.budget_threshold(delta, budget)
+        a = O.route(delta, tau)
+        assert a.sum() <= budget and tau >= 0
+        assert np.isclose(float((a * delta.astype(np.float64)).sum()), best, rtol=1e-6, atol=1e-7)
+    # entries that are NaN escalate whatever tau is and use up budget first
+    d = np.array([0.5, np.nan, 2.0, 1.0, np.nan], np.float32)
+    assert O.budget_threshold(d, 1) == float("inf") and O.route(d, np.inf).tolist() == [0, 1, 0, 0, 1]
+    assert O.budget_threshold(d, 3) == 1.0 and O.route(d, 1.0).sum() == 3
+    assert O.budget_threshold(d, 9) == 0.0
+
+
 # ----------------------------------------------------------------------- stored values
 
 def _golden(name):
