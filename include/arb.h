@@ -167,6 +167,28 @@ arb_status arb_advantage_route(const float *s_t, const float *s_d, int32_t n, fl
  * +inf.  One workgroup; meant for n = number of reasoning steps. */
 arb_status arb_budget_threshold(const float *delta, int32_t n, int32_t budget, float *tau_out, void *stream);
 
+/* ---- the steps of Alg. 1 on either side of the scoring: next-token choice and step boundaries ---- */
+
+/* Next token of n sequences (Alg. 1 "sample z ~ q(. | x)"; Section 3.1): logits = hidden[rows[i]] . w_lm^T,
+ * then, per row, greedy choice (temperature <= 0: smallest index of the maximum) or a draw from
+ * softmax(logits / temperature) by inversion with the caller's uniforms[i] in [0, 1) (the smallest k whose
+ * cumulative weight reaches uniforms[i] times the total).
+ *   hidden  device bf16 [*, d_model]: final-normed hidden states as arb_prefill / arb_score_steps emit them
+ *   rows    device int32 [n]: the row of each sequence's last token
+ *   w_lm    device bf16 [vocab, d_model]; vocab must be a multiple of 128, d_model of 64
+ *   token   device int32 [n]; chosen_logit device fp32 [n] or NULL: the logit of the chosen token
+ *   ws      device workspace of at least arb_next_token_workspace_bytes(n, d_model, vocab) */
+size_t arb_next_token_workspace_bytes(int32_t n, int32_t d_model, int32_t vocab);
+arb_status arb_next_token(const void *hidden, const int32_t *rows, int32_t n, int32_t d_model, const void *w_lm,
+                          int32_t vocab, float temperature, const float *uniforms, int32_t *token,
+                          float *chosen_logit, void *ws, size_t ws_bytes, void *stream);
+
+/* Length of each generated step (Alg. 1: a step ends with the first separator or end-of-sequence token):
+ * tokens device int32 [n, max_len]; len[i] = index of the first sep/eos + 1, or max_len if there is none;
+ * ended[i] (device uint8, may be NULL) = 1 iff that token is eos. */
+arb_status arb_first_stop(const int32_t *tokens, int32_t n, int32_t max_len, int32_t sep, int32_t eos, int32_t *len,
+                          uint8_t *ended, void *stream);
+
 /* Pool slot of every step token, slot = block_tables[b][pos/kv_block]*kv_block + pos%kv_block with
  * pos = prefix_lens[b] + i, as the forward computes it.  slots: device int32 [total_tokens]. */
 arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream);
@@ -177,7 +199,8 @@ arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *s
 typedef enum {
   ARB_EPI_STORE_BF16 = 0,   /* C bf16 [M, N] = A B^T */
   ARB_EPI_RESIDUAL_F32 = 1, /* C fp32 [M, N] += A B^T */
-  ARB_EPI_SWIGLU_BF16 = 2   /* B is [2F, K] (gate rows, up rows); C bf16 [M, F] = silu(A Bg^T) * (A Bu^T); N = F */
+  ARB_EPI_SWIGLU_BF16 = 2,  /* B is [2F, K] (gate rows, up rows); C bf16 [M, F] = silu(A Bg^T) * (A Bu^T); N = F */
+  ARB_EPI_STORE_F32 = 3     /* C fp32 [M, N] = A B^T (logits of the LM head) */
 } arb_gemm_epilogue;
 
 /* Projection GEMM: A bf16 [M, K] row-major, B bf16 [N, K] row-major (weights),

@@ -344,3 +344,50 @@ def budget_threshold(delta, budget: int) -> float:
         return float("inf")
     return float(max(kth, 0.0))
 
+
+# ------------------------------------------------------------- the loop around the scoring (Algorithm 1)
+
+def lm_logits(hidden_rows: np.ndarray, w_lm) -> np.ndarray:
+    """Next-token logits of the final-normed hidden states of the last tokens: h . W_lm^T."""
+    return np.asarray(hidden_rows, dtype=F) @ as_float(w_lm).T
+
+
+def choose_token(logits: np.ndarray, temperature: float = 0.0, u: Optional[float] = None) -> int:
+    """Greedy choice (temperature <= 0: first index of the maximum) or a draw from
+    softmax(logits / temperature) by inversion: the smallest k whose cumulative
+    probability reaches u (u in [0, 1))."""
+    l = np.asarray(logits, dtype=F)
+    if not temperature > 0:
+        return int(np.argmax(l))
+    w = np.exp((l - l.max()) / temperature)
+    c = np.cumsum(w)
+    k = int(np.searchsorted(c, u * c[-1], side="left"))
+    return min(k, l.size - 1)
+
+
+def first_stop(tokens, sep: int, eos: int):
+    """(length, ended): a step runs up to and including its first separator or
+    end-of-sequence token (Algorithm 1); all of `tokens` if there is none."""
+    for i, t in enumerate(tokens):
+        if t == sep or t == eos:
+            return i + 1, t == eos
+    return len(tokens), False
+
+
+def arbitrage_inference(question, draft_step, router_score, target_step, tau: float, eos: int, max_steps: int):
+    """Algorithm 1.  draft_step(x) / target_step(x) return the tokens of one reasoning
+    step generated from context x (ending with the separator or eos); router_score(x, z)
+    returns y_hat.  Returns the final sequence and, per step, (y_hat, escalated)."""
+    x = list(question)
+    log = []
+    for _ in range(max_steps):
+        if x and x[-1] == eos:
+            break
+        z_d = list(draft_step(x))
+        y_hat = router_score(x, z_d)
+        escalate = bool(route(np.array([y_hat]), tau)[0])
+        z = list(target_step(x)) if escalate else z_d
+        x = x + z
+        log.append((y_hat, escalate))
+    return x, log
+

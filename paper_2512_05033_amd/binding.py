@@ -19,13 +19,13 @@ _lib = None
 ARB_OK, ARB_EINVAL, ARB_ESHAPE, ARB_ECAPACITY, ARB_EHIP, ARB_EUNSUPPORTED = range(6)
 ARB_POOL_MEAN, ARB_POOL_LAST = 0, 1
 ARB_ESCALATE_IF_GT, ARB_ACCEPT_IF_GT = 0, 1
-ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16 = 0, 1, 2
+ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16, ARB_EPI_STORE_F32 = 0, 1, 2, 3
 (ARB_STAGE_QKV, ARB_STAGE_ATTENTION, ARB_STAGE_OPROJ, ARB_STAGE_GATE_UP, ARB_STAGE_DOWN, ARB_STAGE_NORM,
  ARB_STAGE_ROPE_APPEND, ARB_STAGE_GATE_UP_LARGE) = range(8)
 _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4: "ARB_EHIP", 5: "ARB_EUNSUPPORTED"}
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
-           "arb_route", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
+           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
            "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
@@ -82,6 +82,12 @@ def load_library(path: Optional[str] = None):
     lib.arb_advantage_route.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p]
     lib.arb_budget_threshold.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.arb_next_token_workspace_bytes.argtypes = [C.c_int32] * 3
+    lib.arb_next_token_workspace_bytes.restype = C.c_size_t
+    lib.arb_next_token.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_float,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_first_stop.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                   C.c_void_p]
     lib.arb_slot_mapping.argtypes = [C.POINTER(_Batch), C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p]
@@ -101,7 +107,8 @@ def load_library(path: Optional[str] = None):
     lib.arb_gemm_large_tile_columns.argtypes = [C.c_int32] * 4
     lib.arb_gemm_large_tile_columns.restype = C.c_int32
     for name in EXPORTS:
-        if name not in ("arb_last_error", "arb_workspace_bytes", "arb_model_trace_count", "arb_gemm_large_tile_columns"):
+        if name not in ("arb_last_error", "arb_workspace_bytes", "arb_model_trace_count", "arb_gemm_large_tile_columns",
+                        "arb_next_token_workspace_bytes"):
             getattr(lib, name).restype = C.c_int
     if path == _LIB_PATH:
         _lib = lib
@@ -265,6 +272,37 @@ def arb_budget_threshold(delta: torch.Tensor, budget: int, stream=None) -> torch
     return out
 
 
+def arb_next_token(hidden: torch.Tensor, rows: torch.Tensor, w_lm: torch.Tensor, temperature: float = 0.0,
+                   uniforms: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None):
+    """-> (token int32 [n], chosen logit fp32 [n]) for the hidden rows `rows` (int32 device tensor)."""
+    _dev(hidden, torch.bfloat16), _dev(rows, torch.int32), _dev(w_lm, torch.bfloat16)
+    n, d, V = rows.numel(), hidden.shape[1], w_lm.shape[0]
+    if w_lm.shape[1] != d:
+        raise ValueError("LM head width")
+    if uniforms is not None:
+        _dev(uniforms, torch.float32)
+    lib = load_library()
+    need = int(lib.arb_next_token_workspace_bytes(n, d, V))
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+    token = torch.empty(n, dtype=torch.int32, device=hidden.device)
+    chosen = torch.empty(n, dtype=torch.float32, device=hidden.device)
+    _check(lib.arb_next_token(_ptr(hidden), _ptr(rows), n, d, _ptr(w_lm), V, float(temperature), _ptr(uniforms),
+                              _ptr(token), _ptr(chosen), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return token, chosen
+
+
+def arb_first_stop(tokens: torch.Tensor, sep: int, eos: int, stream=None):
+    """tokens int32 [n, max_len] -> (len int32 [n], ended uint8 [n])."""
+    _dev(tokens, torch.int32)
+    n, S = tokens.shape
+    length = torch.empty(n, dtype=torch.int32, device=tokens.device)
+    ended = torch.empty(n, dtype=torch.uint8, device=tokens.device)
+    _check(load_library().arb_first_stop(_ptr(tokens), n, S, int(sep), int(eos), _ptr(length), _ptr(ended),
+                                         _stream(stream)))
+    return length, ended
+
+
 def arb_slot_mapping(batch: DeviceBatch, kv_block: int = 16, stream=None) -> torch.Tensor:
     out = torch.empty(batch.total_tokens, dtype=torch.int32, device=batch.tables.device)
     _check(load_library().arb_slot_mapping(C.byref(batch.c), kv_block, _ptr(out), _stream(stream)))
@@ -282,8 +320,8 @@ def arb_stage_gemm(a: torch.Tensor, b: torch.Tensor, epilogue: int = ARB_EPI_STO
     if out is None:
         if epilogue == ARB_EPI_RESIDUAL_F32:
             raise ValueError("the residual epilogue accumulates into `out`")
-        out = torch.empty(M, N, dtype=torch.bfloat16, device=a.device)
-    _dev(out, torch.float32 if epilogue == ARB_EPI_RESIDUAL_F32 else torch.bfloat16)
+        out = torch.empty(M, N, dtype=torch.float32 if epilogue == ARB_EPI_STORE_F32 else torch.bfloat16, device=a.device)
+    _dev(out, torch.float32 if epilogue in (ARB_EPI_RESIDUAL_F32, ARB_EPI_STORE_F32) else torch.bfloat16)
     if tuple(out.shape) != (M, N):
         raise ValueError("output shape")
     _check(load_library().arb_stage_gemm(_ptr(a), _ptr(b), _ptr(out), M, N, K, epilogue, _stream(stream)))

@@ -343,6 +343,38 @@ extern "C" arb_status arb_budget_threshold(const float *delta, int32_t n, int32_
   return launch_budget_threshold(delta, n, budget, tau_out, (hipStream_t)stream);
 }
 
+extern "C" size_t arb_next_token_workspace_bytes(int32_t n, int32_t d_model, int32_t vocab) {
+  if (n < 0 || d_model <= 0 || vocab <= 0) return 0;
+  return align_up((size_t)n * d_model * sizeof(bf16), 256) + align_up((size_t)n * vocab * sizeof(float), 256);
+}
+
+extern "C" arb_status arb_next_token(const void *hidden, const int32_t *rows, int32_t n, int32_t d_model,
+                                     const void *w_lm, int32_t vocab, float temperature, const float *uniforms,
+                                     int32_t *token, float *chosen_logit, void *ws, size_t ws_bytes, void *stream) {
+  if (n < 0) return arb_fail(ARB_EINVAL, "arb_next_token: n = %d", n);
+  if (n == 0) return ARB_OK;
+  if (!hidden || !rows || !w_lm || !token) return arb_fail(ARB_EINVAL, "arb_next_token: null pointer");
+  if (d_model <= 0 || vocab <= 0) return arb_fail(ARB_ESHAPE, "arb_next_token: d_model %d, vocab %d", d_model, vocab);
+  if (temperature > 0.f && !uniforms) return arb_fail(ARB_EINVAL, "arb_next_token: sampling needs uniforms");
+  const size_t need = arb_next_token_workspace_bytes(n, d_model, vocab);
+  if (!ws || ws_bytes < need) return arb_fail(ARB_ECAPACITY, "arb_next_token: workspace %zu < %zu bytes", ws_bytes, need);
+  bf16 *x = (bf16 *)ws;
+  float *logits = (float *)((char *)ws + align_up((size_t)n * d_model * sizeof(bf16), 256));
+  hipStream_t st = (hipStream_t)stream;
+  arb_status s;
+  if ((s = launch_gather_rows((const bf16 *)hidden, rows, n, d_model, x, st))) return s;
+  if ((s = launch_gemm(x, (const bf16 *)w_lm, logits, n, vocab, d_model, ARB_EPI_STORE_F32, st))) return s;
+  return launch_sample_token(logits, n, vocab, temperature, uniforms, token, chosen_logit, st);
+}
+
+extern "C" arb_status arb_first_stop(const int32_t *tokens, int32_t n, int32_t max_len, int32_t sep, int32_t eos,
+                                     int32_t *len, uint8_t *ended, void *stream) {
+  if (n < 0 || max_len < 0) return arb_fail(ARB_EINVAL, "arb_first_stop: n = %d, max_len = %d", n, max_len);
+  if (n == 0) return ARB_OK;
+  if (!len || (max_len > 0 && !tokens)) return arb_fail(ARB_EINVAL, "arb_first_stop: null pointer");
+  return launch_first_stop(tokens, n, max_len, sep, eos, len, ended, (hipStream_t)stream);
+}
+
 extern "C" arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream) {
   BatchInfo info;
   if (kv_block <= 0) return arb_fail(ARB_EINVAL, "arb_slot_mapping: kv_block %d", kv_block);

@@ -87,3 +87,8 @@ arb_status launch_route(const float *scores, int n, float tau, int sense, uint8_
 arb_status launch_advantage_route(const float *s_t, const float *s_d, int n, float tau, const float *tau_device,
                                float *delta, uint8_t *escalate, float *realized, hipStream_t st);
 arb_status launch_budget_threshold(const float *delta, int n, int budget, float *tau_out, hipStream_t st);
+arb_status launch_gather_rows(const bf16 *src, const int32_t *rows, int n, int d, bf16 *dst, hipStream_t st);
+arb_status launch_sample_token(const float *logits, int n, int V, float temperature, const float *uniforms,
+                               int32_t *token, float *chosen, hipStream_t st);
+arb_status launch_first_stop(const int32_t *tokens, int n, int S, int sep, int eos, int32_t *len, uint8_t *ended,
+                             hipStream_t st);

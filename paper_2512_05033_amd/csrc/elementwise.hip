@@ -390,3 +390,132 @@ arb_status launch_budget_threshold(const float *delta, int n, int budget, float 
   return ARB_OK;
 }
 
+// ------------------------------------------------------- next-token choice (LM head)
+
+// Rows rows[i] of a bf16 [*, d] matrix, copied to a dense [n, d] matrix (the last step token of each
+// sequence, as input of the LM head GEMM).
+__global__ void gather_rows_kernel(const bf16 *__restrict__ src, const int32_t *__restrict__ rows, int d,
+                                   bf16 *__restrict__ dst) {
+  const int i = blockIdx.x;
+  const bf16 *s = src + (size_t)rows[i] * d;
+  for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) *(bf16x8 *)(dst + (size_t)i * d + c) = *(const bf16x8 *)(s + c);
+}
+
+arb_status launch_gather_rows(const bf16 *src, const int32_t *rows, int n, int d, bf16 *dst, hipStream_t st) {
+  if (n == 0) return ARB_OK;
+  if (d % 8 != 0) return arb_fail(ARB_EUNSUPPORTED, "gather_rows: width %d is not a multiple of 8", d);
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(n), dim3(256), 0, st, src, rows, d, dst);
+  ARB_CHECK_LAUNCH("gather_rows");
+  return ARB_OK;
+}
+
+// One block per row of fp32 logits [n, V].  Greedy (temperature <= 0): the smallest index of the
+// maximum.  Otherwise the token is drawn from softmax(logits / temperature) by inversion with the
+// caller's uniform u in [0, 1): the smallest k with sum_{i<=k} w_i >= u * sum_i w_i, where
+// w_i = exp((l_i - max) / temperature); sums run in index order within a thread's contiguous range
+// and in thread order across ranges, so a call is reproducible.
+__global__ __launch_bounds__(256) void sample_token_kernel(const float *__restrict__ logits, int V, float temperature,
+                                                           const float *__restrict__ uniforms,
+                                                           int32_t *__restrict__ token, float *__restrict__ chosen) {
+  __shared__ float red_v[256];
+  __shared__ int red_i[256];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const float *l = logits + (size_t)row * V;
+  const int per = (V + 255) / 256, lo = min(tid * per, V), hi = min(lo + per, V);    // contiguous range of this thread
+  float best = -INFINITY;
+  int arg = V;
+  for (int i = lo; i < hi; ++i) {
+    const float v = l[i];
+    if (v > best) { best = v; arg = i; }
+  }
+  red_v[tid] = best;
+  red_i[tid] = arg;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) {
+      const float v = red_v[tid + o];
+      const int a = red_i[tid + o];
+      if (v > red_v[tid] || (v == red_v[tid] && a < red_i[tid])) { red_v[tid] = v; red_i[tid] = a; }
+    }
+    __syncthreads();
+  }
+  const float mx = red_v[0];
+  const int amax = red_i[0] < V ? red_i[0] : 0;          // a row of NaNs or -inf picks token 0
+  __syncthreads();
+  if (!(temperature > 0.f)) {
+    if (tid == 0) {
+      token[row] = amax;
+      if (chosen) chosen[row] = l[amax];
+    }
+    return;
+  }
+  const float inv_t = 1.0f / temperature;
+  __shared__ float total_s;
+  __shared__ int pick_s;
+  float part = 0.f;
+  for (int i = lo; i < hi; ++i) part += expf((l[i] - mx) * inv_t);
+  red_v[tid] = part;
+  __syncthreads();
+  if (tid == 0) {                                       // exclusive prefix over the 256 ranges, in order
+    float run = 0.f;
+    for (int t = 0; t < 256; ++t) {
+      const float p = red_v[t];
+      red_v[t] = run;
+      run += p;
+    }
+    total_s = run;
+    pick_s = V;
+  }
+  __syncthreads();
+  const float target = uniforms[row] * total_s;
+  const float before = red_v[tid];
+  // the range that contains the target: before < target <= before + part (the first range also takes target == 0)
+  if (lo < hi && (target > before || tid == 0) && target <= before + part) {
+    float run = before;
+    int pick = hi - 1;                                  // rounding in the re-summation cannot leave the range
+    for (int i = lo; i < hi; ++i) {
+      run += expf((l[i] - mx) * inv_t);
+      if (run >= target) { pick = i; break; }
+    }
+    atomicMin(&pick_s, pick);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int k = pick_s < V ? pick_s : amax;           // no range claimed the target (rounding at the very end): the mode
+    token[row] = k;
+    if (chosen) chosen[row] = l[k];
+  }
+}
+
+arb_status launch_sample_token(const float *logits, int n, int V, float temperature, const float *uniforms,
+                               int32_t *token, float *chosen, hipStream_t st) {
+  if (n == 0) return ARB_OK;
+  hipLaunchKernelGGL(sample_token_kernel, dim3(n), dim3(256), 0, st, logits, V, temperature, uniforms, token, chosen);
+  ARB_CHECK_LAUNCH("sample_token");
+  return ARB_OK;
+}
+
+// Length of a generated step (Alg. 1: tokens up to and including the first separator or
+// end-of-sequence token) for each row of tokens [n, S]; S if neither occurs.
+__global__ void first_stop_kernel(const int32_t *__restrict__ tokens, int n, int S, int sep, int eos,
+                                  int32_t *__restrict__ len, uint8_t *__restrict__ ended) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= n) return;
+  int L = S;
+  uint8_t e = 0;
+  for (int i = 0; i < S; ++i) {
+    const int t = tokens[(size_t)b * S + i];
+    if (t == sep || t == eos) { L = i + 1; e = t == eos; break; }
+  }
+  len[b] = L;
+  if (ended) ended[b] = e;
+}
+
+arb_status launch_first_stop(const int32_t *tokens, int n, int S, int sep, int eos, int32_t *len, uint8_t *ended,
+                             hipStream_t st) {
+  if (n == 0) return ARB_OK;
+  hipLaunchKernelGGL(first_stop_kernel, dim3(ceil_div(n, 64)), dim3(64), 0, st, tokens, n, S, sep, eos, len, ended);
+  ARB_CHECK_LAUNCH("first_stop");
+  return ARB_OK;
+}
+

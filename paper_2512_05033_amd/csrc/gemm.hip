@@ -47,8 +47,8 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {   // element offset
   return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
-// Internal epilogue: split s of a split-K launch stores its fp32 partial product to C + s*M*N.
-constexpr int EPI_PARTIAL_F32 = 3;
+// fp32 store; in a split-K launch split s stores its partial product to C + s*M*N.
+constexpr int EPI_PARTIAL_F32 = ARB_EPI_STORE_F32;
 
 template <int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
@@ -375,6 +375,8 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
           if (m < M) {
             if (EPI == ARB_EPI_STORE_BF16) {
               ((bf16 *)Cv)[(size_t)m * N + col] = (bf16)acc[i][j][r];
+            } else if (EPI == ARB_EPI_STORE_F32) {
+              ((float *)Cv)[(size_t)m * N + col] = acc[i][j][r];
             } else {
               float *dst = (float *)Cv + (size_t)m * N + col;
               *dst += acc[i][j][r];
@@ -434,6 +436,7 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
     switch (epilogue) {
       case ARB_EPI_STORE_BF16: ARB_BIG(ARB_EPI_STORE_BF16); break;
       case ARB_EPI_RESIDUAL_F32: ARB_BIG(ARB_EPI_RESIDUAL_F32); break;
+      case ARB_EPI_STORE_F32: ARB_BIG(ARB_EPI_STORE_F32); break;
       case ARB_EPI_SWIGLU_BF16: ARB_BIG(ARB_EPI_SWIGLU_BF16); break;
       default: return arb_fail(ARB_EINVAL, "gemm: unknown epilogue %d", epilogue);
     }
@@ -451,6 +454,7 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
       if (splits > 1) ARB_SMALL(EPI_PARTIAL_F32); else ARB_SMALL(ARB_EPI_RESIDUAL_F32);
       break;
     case ARB_EPI_SWIGLU_BF16: ARB_SMALL(ARB_EPI_SWIGLU_BF16); break;
+    case ARB_EPI_STORE_F32: ARB_SMALL(ARB_EPI_STORE_F32); break;
     default: return arb_fail(ARB_EINVAL, "gemm: unknown epilogue %d", epilogue);
   }
 #undef ARB_SMALL

@@ -209,6 +209,50 @@ def test_advantage_route_and_budget_threshold(A):
     assert A.arb_advantage_route(torch.empty(0, device="cuda"), torch.empty(0, device="cuda"))[1].numel() == 0
 
 
+@pytest.mark.parametrize("d,V,n", [(256, 32000, 4), (1536, 151936, 16), (256, 32000, 130)])
+def test_next_token_greedy_and_sampled(A, d, V, n):
+    """LM head + choice against the oracle.  Where rounding can move the choice (near-equal
+    logits, a uniform next to a boundary of the cumulative distribution) any index the exact
+    arithmetic admits within 1e-4 is valid; the logit reported for the choice must match."""
+    hidden = rand_bf16((n + 37, d), 1.0, 41)
+    rows = torch.from_numpy(np.random.default_rng(d).permutation(n + 37)[:n].astype(np.int32)).cuda()
+    w_lm = rand_bf16((V, d), 0.02, 42)
+    logits = O.lm_logits(bf16_np(hidden)[rows.cpu().numpy()], W.bf16_bits(w_lm))
+    tok, chosen = A.arb_next_token(hidden, rows, w_lm)
+    tok, chosen = tok.cpu().numpy(), chosen.cpu().numpy()
+    for i in range(n):
+        assert logits[i, tok[i]] >= logits[i].max() - 1e-4
+        assert abs(chosen[i] - logits[i, tok[i]]) < 1e-4
+        if logits[i].max() - np.partition(logits[i], -2)[-2] > 1e-3:
+            assert tok[i] == O.choose_token(logits[i])
+    T = 0.8
+    u = np.random.default_rng(V).random(n).astype(np.float32)
+    u[0] = 0.0
+    tok, chosen = A.arb_next_token(hidden, rows, w_lm, temperature=T, uniforms=torch.from_numpy(u).cuda())
+    tok = tok.cpu().numpy()
+    exact = 0
+    for i in range(n):
+        w = np.exp((logits[i] - logits[i].max()) / T)
+        c = np.cumsum(w)
+        target, k = float(u[i]) * c[-1], int(tok[i])
+        assert (c[k - 1] if k else 0.0) - 1e-4 * c[-1] <= target <= c[k] + 1e-4 * c[-1], (i, k)
+        exact += k == O.choose_token(logits[i], T, float(u[i]))
+    assert exact >= n - max(1, n // 50) and tok[0] == 0
+
+
+def test_first_stop_bit_exact(A):
+    r = np.random.default_rng(8)
+    toks = r.integers(3, 50, (70, 33)).astype(np.int32)
+    toks[0, :] = 7                      # no stop token
+    toks[1, 0] = 1                      # separator first
+    toks[2, 32] = 2                     # eos last
+    toks[3, 5], toks[3, 4] = 1, 2       # eos before a separator
+    length, ended = A.arb_first_stop(torch.from_numpy(toks).cuda(), sep=1, eos=2)
+    want = [O.first_stop(list(row), 1, 2) for row in toks]
+    assert length.cpu().tolist() == [w[0] for w in want] and ended.cpu().tolist() == [int(w[1]) for w in want]
+    assert [w[0] for w in want[:4]] == [33, 1, 33, 5]
+
+
 # ---------------------------------------------------------------------- attention
 
 def _attention_case(A, shape, prefix, steps, peaky, seed):

@@ -508,6 +508,61 @@ def test_budget_threshold_attains_the_brute_force_optimum(n, seed):
     assert O.budget_threshold(d, 9) == 0.0
 
 
+def test_choose_token_greedy_and_inversion_sampling():
+    r = np.random.default_rng(3)
+    logits = r.normal(0, 2, 50)
+    assert O.choose_token(logits) == int(np.argmax(logits)) == O.choose_token(logits, 0.0)
+    assert O.choose_token(np.array([1.0, 3.0, 3.0, 2.0])) == 1                  # first index of the maximum
+    # inversion: monotone in u, u = 0 gives token 0, and the frequencies over a fine grid of u are
+    # the softmax probabilities (torch library softmax as the independent formulation)
+    T = 0.7
+    us = (np.arange(200000) + 0.5) / 200000
+    ks = np.array([O.choose_token(logits[:8], T, u) for u in us[::40]])
+    assert np.all(np.diff(ks) >= 0) and O.choose_token(logits[:8], T, 0.0) == 0
+    freq = np.bincount(ks, minlength=8) / ks.size
+    p = torch.softmax(torch.tensor(logits[:8], dtype=torch.float64) / T, 0).numpy()
+    assert np.abs(freq - p).max() < 2e-3
+    # temperature -> 0 approaches greedy; a very high temperature approaches uniform
+    assert O.choose_token(logits, 1e-3, 0.5) == int(np.argmax(logits))
+    assert O.choose_token(logits, 1e6, 0.999) == 49
+
+
+def test_first_stop_and_lm_logits():
+    assert O.first_stop([5, 6, 9, 7, 8], sep=9, eos=8) == (3, False)
+    assert O.first_stop([5, 8, 9], sep=9, eos=8) == (2, True)
+    assert O.first_stop([5, 6], sep=9, eos=8) == (2, False) and O.first_stop([], 9, 8) == (0, False)
+    h = np.array([[1.0, 2.0], [0.5, -1.0]])
+    w = O.float_to_bf16(np.array([[1.0, 0.0], [0.0, 1.0], [2.0, 2.0]]))
+    assert np.array_equal(O.lm_logits(h, w), np.array([[1.0, 2.0, 6.0], [0.5, -1.0, -1.0]]))
+
+
+def test_arbitrage_inference_follows_algorithm_1():
+    SEP, EOS = 1, 2
+    calls = []
+    def draft(x):
+        calls.append(("d", len(x)))
+        return [10 + len(x), SEP]
+    def target(x):
+        calls.append(("t", len(x)))
+        return [90, EOS] if len(x) >= 11 else [50 + len(x), 51, SEP]
+    # y_hat = 0.5 exactly at the second step (a tie accepts), above tau at the third, below otherwise
+    scores = iter([0.1, 0.5, 0.9, 0.2, 0.9])
+    def router(x, z):
+        calls.append(("r", len(x), tuple(z)))
+        return next(scores)
+    x, log = O.arbitrage_inference([7, 8 + 1], draft, router, target, tau=0.5, eos=EOS, max_steps=10)
+    # steps: accept, accept (tie), escalate (target step of 3 tokens from the same prefix), accept, escalate -> eos
+    assert [e for _, e in log] == [False, False, True, False, True]
+    assert x == [7, 9, 12, SEP, 14, SEP, 56, 51, SEP, 19, SEP, 90, EOS]
+    # the target regenerates from the same prefix the draft saw; the router sees the draft's step
+    assert ("d", 6) in calls and ("t", 6) in calls and ("r", 6, (16, SEP)) in calls
+    # stops at eos without another draft call, and at max_steps
+    assert calls[-1][0] == "t" and len(log) == 5
+    x2, log2 = O.arbitrage_inference([7], draft, lambda x, z: 0.0, target, tau=0.5, eos=EOS, max_steps=3)
+    assert len(log2) == 3 and x2 == [7, 11, SEP, 13, SEP, 15, SEP]
+    assert O.arbitrage_inference([7, EOS], draft, router, target, 0.5, EOS, 5) == ([7, EOS], [])
+
+
 # ----------------------------------------------------------------------- stored values
 
 def _golden(name):
