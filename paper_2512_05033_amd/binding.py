@@ -196,7 +196,10 @@ class DeviceBatch:
         tables = np.ascontiguousarray(block_tables, dtype=np.int32)
         to = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
         self.prefix, self.cu, self.tables = to(self.prefix_host), to(self.cu_host), to(tables)
-        self.tokens = None if token_ids is None else to(token_ids)
+        if isinstance(token_ids, torch.Tensor):           # already on the device (tokens chosen by arb_next_token)
+            self.tokens = _dev(token_ids, torch.int32)
+        else:
+            self.tokens = None if token_ids is None else to(token_ids)
         self.batch = len(self.prefix_host)
         self.total_tokens = int(self.cu_host[-1]) if len(self.cu_host) else 0
         self.c = _Batch(self.batch, self.total_tokens, tables.shape[1] if tables.ndim == 2 else 0,

@@ -527,3 +527,87 @@ def test_empty_batch_and_bad_arguments(A):
     with pytest.raises(A.ArbError) as err:                                   # workspace too small
         A.arb_score_steps(sess.model, sess.kv, sess.dbatch, 0.0, ws=sess.ws[:1024])
     assert err.value.status == A.ARB_ECAPACITY
+
+
+# ------------------------------------------------------------------ Algorithm 1 loop
+
+def _tiny_role(A, name, seed, n_blocks, with_lm):
+    from paper_2512_05033_amd.arbitrage import Role
+    m = W.TINY
+    weights = W.make_weights(m, seed, "cuda", gain_jitter=0.1, b_head=0.0)
+    model = H().make_model(m, weights, has_router_head=not with_lm)
+    shape = (n_blocks, m.n_kv_heads, m.kv_block, m.head_dim)
+    kv = A.KVCache([torch.zeros(shape, dtype=torch.bfloat16, device="cuda") for _ in range(m.n_layers)],
+                   [torch.zeros(shape, dtype=torch.bfloat16, device="cuda") for _ in range(m.n_layers)])
+    w_lm = W.normal_bf16(seed, "lm_head", (m.vocab, m.d_model), 0.02, "cuda") if with_lm else None
+    return Role(name, model, kv, w_lm), weights
+
+
+def _oracle_hidden(weights, tokens):
+    """Final-normed hidden states of a whole sequence by the oracle, from an empty cache."""
+    m, p = oracle_model(W.TINY), oracle_params(weights)
+    n = len(tokens)
+    nb = (n + 15) // 16
+    shape = (nb, W.TINY.n_kv_heads, 16, W.TINY.head_dim)
+    kp = [np.zeros(shape, np.uint16) for _ in range(m.n_layers)]
+    vp = [np.zeros(shape, np.uint16) for _ in range(m.n_layers)]
+    return O.forward(m, p, kp, vp, np.asarray(tokens, np.int32), np.zeros(1, np.int32), np.array([0, n], np.int32),
+                     np.arange(nb, dtype=np.int32)[None, :])
+
+
+def test_arbitrage_loop_replayed_by_the_oracle(A):
+    """Alg. 1 on the device for three questions, then replayed by the oracle: every generated token
+    must be a maximiser of the oracle's logits for the same history (within the bf16 forward's error),
+    every router score must match, and the oracle's own Algorithm 1, fed the recorded steps and its
+    own scores, must arrive at the same sequences."""
+    from paper_2512_05033_amd.arbitrage import Arbitrage
+    S, steps, B = 5, 3, 3
+    questions = [[int(t) for t in W.uniform_ints(77, f"q{b}", n, W.TINY.vocab).numpy()] for b, n in enumerate((5, 9, 17))]
+    blocks_per_seq = (17 + steps * S + 15) // 16 + 1
+    tables = np.random.default_rng(3).permutation(B * blocks_per_seq).astype(np.int32).reshape(B, blocks_per_seq)
+    def run(tau, sep):
+        trace = []
+        roles, weights = {}, {}
+        for name, seed, lm in (("draft", 101, True), ("target", 202, True), ("router", 303, False)):
+            roles[name], weights[name] = _tiny_role(A, name, seed, B * blocks_per_seq, lm)
+        arb = Arbitrage(roles["draft"], roles["target"], roles["router"], tables, tau=tau, sep=sep, eos=-5,
+                        max_step_tokens=S, trace=trace)
+        out, log = arb.run(questions, steps)
+        return out, log, trace, roles, weights
+    # a first pass picks a separator the draft really emits and a threshold that splits the scores
+    _, log0, trace0, _, _ = run(tau=1e9, sep=-7)
+    sep = [e for e in trace0 if e[0] == "step" and e[1] == "draft"][1][4][2]
+    tau = float(np.median([s for b in log0 for s, _ in log0[b]]))
+    out, log, trace, roles, weights = run(tau, sep)
+    decisions = [e for b in log for _, e in log[b]]
+    assert any(decisions) and not all(decisions)                        # both branches of Alg. 1 are taken
+    assert any(len(e[4]) < S for e in trace if e[0] == "step")           # some step ends at the separator
+    TOL = 3e-2
+    recorded = {}
+    for ev in trace:
+        if ev[0] == "step":
+            _, name, b, ctx, toks = ev
+            assert 1 <= len(toks) <= S and all(t != sep for t in toks[:-1])
+            assert toks[-1] == sep or len(toks) == S
+            hidden = _oracle_hidden(weights[name], ctx + toks)
+            logits = O.lm_logits(hidden[len(ctx) - 1:len(ctx) - 1 + len(toks)], W.bf16_bits(roles[name].w_lm))
+            for i, t in enumerate(toks):
+                assert logits[i, t] >= logits[i].max() - TOL, (name, b, i)
+            recorded[(name, tuple(ctx))] = toks
+    oracle_scores = {}
+    for ev in trace:
+        if ev[0] == "route":
+            _, b, ctx, z, score, esc = ev
+            y = _oracle_hidden(weights["router"], ctx + z)[len(ctx):]
+            w_head = oracle_params(weights["router"]).w_head
+            ref = float(O.router_scores(y, np.array([0, len(z)]), w_head, 0.0)[0])
+            assert abs(score - ref) < SCORE_TOL
+            if abs(ref - tau) >= SCORE_TOL:
+                assert esc == bool(O.route(np.array([ref]), tau)[0])
+            oracle_scores[(tuple(ctx), tuple(z))] = ref if abs(ref - tau) >= SCORE_TOL else score
+    for b, q in enumerate(questions):
+        x, olog = O.arbitrage_inference(q, lambda x: recorded[("draft", tuple(x))],
+                                        lambda x, z: oracle_scores[(tuple(x), tuple(z))],
+                                        lambda x: recorded[("target", tuple(x))], tau, -5, steps)
+        assert x == out[b] and [e for _, e in olog] == [e for _, e in log[b]]
+
