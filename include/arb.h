@@ -88,6 +88,11 @@ typedef struct {
   const float *g_final;
   const float *w_head;
   float b_head;
+  /* 4-bit projection weights (the weight-quantized draft of Section 5.1).  NULL (all four): the projection
+   * weights above are bf16.  Otherwise HOST arrays of n_layers DEVICE pointers to bf16 scales
+   * [rows, in/128], and wqkv/wo/wgu/wd point at the packed integers uint32 [rows, in/8] of
+   * arb_w4_quantize instead of bf16 values (same row order).  Embedding, gains and head stay as above. */
+  const void *const *wqkv_scale, *const *wo_scale, *const *wgu_scale, *const *wd_scale;
 } arb_weights;
 
 /* Paged KV cache.  k_pool / v_pool are HOST arrays of n_layers DEVICE pointers;
@@ -207,6 +212,19 @@ typedef enum {
  * fp32 accumulation.  K % 64 == 0 and N % 128 == 0 (N % 64 == 0 for SWIGLU). */
 arb_status arb_stage_gemm(const void *A, const void *B, void *C, int32_t M, int32_t N, int32_t K, int32_t epilogue,
                           void *stream);
+
+/* 4-bit weight format of the quantized draft (Section 5.1; the paper takes its integers from GPTQ /
+ * llama.cpp, the forward only needs integers and group scales): per row and group of 128 consecutive
+ * inputs, scale = bf16(max|w| / 7), q = clip(rint(w / scale), -8, 7) (0 where scale is 0; fp32
+ * quotients, round half to even); stored as q + 8 in nibbles, eight consecutive inputs per uint32 from
+ * the least significant nibble up.  W device bf16 [N, K], K % 128 == 0; packed device uint32 [N, K/8];
+ * scales device bf16 [N, K/128]. */
+arb_status arb_w4_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream);
+
+/* arb_stage_gemm with such weights: C = A W'^T, W'[n,k] = q[n,k] * scale[n, k/128] (no rounding of the
+ * products; fp32 accumulation).  K % 128 == 0; N and epilogues as arb_stage_gemm. */
+arb_status arb_stage_gemm_w4(const void *A, const void *packed, const void *scales, void *C, int32_t M, int32_t N,
+                             int32_t K, int32_t epilogue, void *stream);
 
 /* How the projection GEMM of that shape is launched (host arithmetic only): the number of leading
  * 256-column blocks of C (128-feature blocks for SWIGLU) that one kernel computes in 256x256 tiles; the

@@ -25,7 +25,7 @@ ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16, ARB_EPI_STORE_F32
 _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4: "ARB_EHIP", 5: "ARB_EUNSUPPORTED"}
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
-           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_stage_attention", "arb_stage_rmsnorm",
+           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_w4_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
            "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
@@ -46,7 +46,8 @@ class _Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("wqkv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)),
                 ("wgu", C.POINTER(C.c_void_p)), ("wd", C.POINTER(C.c_void_p)), ("g_attn", C.POINTER(C.c_void_p)),
                 ("g_mlp", C.POINTER(C.c_void_p)), ("g_final", C.c_void_p), ("w_head", C.c_void_p),
-                ("b_head", C.c_float)]
+                ("b_head", C.c_float), ("wqkv_scale", C.POINTER(C.c_void_p)), ("wo_scale", C.POINTER(C.c_void_p)),
+                ("wgu_scale", C.POINTER(C.c_void_p)), ("wd_scale", C.POINTER(C.c_void_p))]
 
 
 class _KV(C.Structure):
@@ -91,6 +92,9 @@ def load_library(path: Optional[str] = None):
     lib.arb_slot_mapping.argtypes = [C.POINTER(_Batch), C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p]
+    lib.arb_w4_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.arb_stage_gemm_w4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_void_p]
     lib.arb_stage_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(_Batch),
                                         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.arb_stage_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -148,15 +152,21 @@ class Model:
         lib = load_library()
         w = weights
         bf, f32 = torch.bfloat16, torch.float32
-        self._keep = [_dev(w.embed, bf), *[_dev(t, bf) for l in (w.wqkv, w.wo, w.wgu, w.wd) for t in l],
+        scales = getattr(w, "scales", None)                   # set: 4-bit projection weights (QuantizedWeights)
+        proj = torch.int32 if scales is not None else bf
+        self._keep = [_dev(w.embed, bf), *[_dev(t, proj) for l in (w.wqkv, w.wo, w.wgu, w.wd) for t in l],
                       *[_dev(t, f32) for l in (w.g_attn, w.g_mlp) for t in l], _dev(w.g_final, f32)]
         if has_router_head:
             self._keep.append(_dev(w.w_head, f32))
         self.cfg = _Cfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rms_eps, rope_base,
                         kv_block, pool, int(has_router_head))
         self._arrays = [_ptr_array(l) for l in (w.wqkv, w.wo, w.wgu, w.wd, w.g_attn, w.g_mlp)]
+        self._scale_arrays = [None] * 4
+        if scales is not None:
+            self._keep += [_dev(t, bf) for l in scales for t in l]
+            self._scale_arrays = [_ptr_array(l) for l in scales]
         cw = _Weights(w.embed.data_ptr(), *self._arrays, w.g_final.data_ptr(),
-                      w.w_head.data_ptr() if has_router_head else None, float(w.b_head))
+                      w.w_head.data_ptr() if has_router_head else None, float(w.b_head), *self._scale_arrays)
         self.handle = C.c_void_p()
         _check(lib.arb_model_create(C.byref(self.cfg), C.byref(cw), C.byref(self.handle)))
         self.weights = w
@@ -329,6 +339,49 @@ def arb_stage_gemm(a: torch.Tensor, b: torch.Tensor, epilogue: int = ARB_EPI_STO
         raise ValueError("output shape")
     _check(load_library().arb_stage_gemm(_ptr(a), _ptr(b), _ptr(out), M, N, K, epilogue, _stream(stream)))
     return out
+
+
+def arb_w4_quantize(w: torch.Tensor, stream=None):
+    """bf16 [N, K] -> (packed int32 [N, K/8] (the uint32 words), scales bf16 [N, K/128])."""
+    _dev(w, torch.bfloat16)
+    N, K = w.shape
+    if K % 128:
+        raise ValueError("K must be a multiple of 128")
+    packed = torch.empty(N, K // 8, dtype=torch.int32, device=w.device)
+    scales = torch.empty(N, K // 128, dtype=torch.bfloat16, device=w.device)
+    _check(load_library().arb_w4_quantize(_ptr(w), N, K, _ptr(packed), _ptr(scales), _stream(stream)))
+    return packed, scales
+
+
+def arb_stage_gemm_w4(a: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, epilogue: int = ARB_EPI_STORE_BF16,
+                      out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """a bf16 [M, K], 4-bit weights of arb_w4_quantize for [N, K] (or [2F, K] for SwiGLU) -> [M, N] (or [M, F])."""
+    _dev(a, torch.bfloat16), _dev(packed, torch.int32), _dev(scales, torch.bfloat16)
+    M, K = a.shape
+    rows = packed.shape[0]
+    N = rows // 2 if epilogue == ARB_EPI_SWIGLU_BF16 else rows
+    if packed.shape[1] * 8 != K or tuple(scales.shape) != (rows, K // 128):
+        raise ValueError("weight shapes")
+    f32_out = epilogue in (ARB_EPI_RESIDUAL_F32, ARB_EPI_STORE_F32)
+    if out is None:
+        if epilogue == ARB_EPI_RESIDUAL_F32:
+            raise ValueError("the residual epilogue accumulates into `out`")
+        out = torch.empty(M, N, dtype=torch.float32 if f32_out else torch.bfloat16, device=a.device)
+    _dev(out, torch.float32 if f32_out else torch.bfloat16)
+    _check(load_library().arb_stage_gemm_w4(_ptr(a), _ptr(packed), _ptr(scales), _ptr(out), M, N, K, epilogue,
+                                            _stream(stream)))
+    return out
+
+
+class QuantizedWeights:
+    """The weights of a model with its four projection matrices per layer in the 4-bit format."""
+
+    def __init__(self, w):
+        self.embed, self.g_attn, self.g_mlp, self.g_final = w.embed, w.g_attn, w.g_mlp, w.g_final
+        self.w_head, self.b_head = w.w_head, w.b_head
+        pairs = [[arb_w4_quantize(t) for t in l] for l in (w.wqkv, w.wo, w.wgu, w.wd)]
+        self.wqkv, self.wo, self.wgu, self.wd = ([p for p, _ in l] for l in pairs)
+        self.scales = [[s for _, s in l] for l in pairs]
 
 
 def arb_gemm_large_tile_columns(M: int, N: int, K: int, epilogue: int) -> int:

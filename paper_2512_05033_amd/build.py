@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libarb.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "elementwise.hip"]
+SOURCES = ["api.hip", "gemm.hip", "gemm_w4.hip", "attention.hip", "elementwise.hip"]
 
 # -packed-fp32-ops off: hipcc must not form v_pk_*_f32 from scalar float code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

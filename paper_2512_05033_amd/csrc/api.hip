@@ -29,7 +29,9 @@ extern "C" const char *arb_last_error(void) { return g_err; }
 struct arb_model {
   arb_model_cfg cfg;
   const bf16 *embed;
-  std::vector<const bf16 *> wqkv, wo, wgu, wd;
+  std::vector<const bf16 *> wqkv, wo, wgu, wd;              // packed uint32 when w4
+  std::vector<const bf16 *> sqkv, so, sgu, sd;              // group scales of 4-bit weights
+  bool w4 = false;
   std::vector<const float *> g_attn, g_mlp;
   const float *g_final, *w_head;
   float b_head;
@@ -67,15 +69,29 @@ extern "C" arb_status arb_model_create(const arb_model_cfg *cfg, const arb_weigh
   for (int l = 0; l < c.n_layers; ++l)
     if (!w->wqkv[l] || !w->wo[l] || !w->wgu[l] || !w->wd[l] || !w->g_attn[l] || !w->g_mlp[l])
       return arb_fail(ARB_EINVAL, "arb_model_create: null weight pointer in layer %d", l);
+  const int n_scale = (w->wqkv_scale != nullptr) + (w->wo_scale != nullptr) + (w->wgu_scale != nullptr) + (w->wd_scale != nullptr);
+  if (n_scale != 0 && n_scale != 4) return arb_fail(ARB_EINVAL, "arb_model_create: either all four scale tables or none");
+  if (n_scale == 4) {
+    for (int l = 0; l < c.n_layers; ++l)
+      if (!w->wqkv_scale[l] || !w->wo_scale[l] || !w->wgu_scale[l] || !w->wd_scale[l])
+        return arb_fail(ARB_EINVAL, "arb_model_create: null scale pointer in layer %d", l);
+  }
   arb_model *m = new (std::nothrow) arb_model;
   if (!m) return arb_fail(ARB_EINVAL, "arb_model_create: out of host memory");
   m->cfg = c;
+  m->w4 = n_scale == 4;
   m->embed = (const bf16 *)w->embed;
   for (int l = 0; l < c.n_layers; ++l) {
     m->wqkv.push_back((const bf16 *)w->wqkv[l]);
     m->wo.push_back((const bf16 *)w->wo[l]);
     m->wgu.push_back((const bf16 *)w->wgu[l]);
     m->wd.push_back((const bf16 *)w->wd[l]);
+    if (m->w4) {
+      m->sqkv.push_back((const bf16 *)w->wqkv_scale[l]);
+      m->so.push_back((const bf16 *)w->wo_scale[l]);
+      m->sgu.push_back((const bf16 *)w->wgu_scale[l]);
+      m->sd.push_back((const bf16 *)w->wd_scale[l]);
+    }
     m->g_attn.push_back(w->g_attn[l]);
     m->g_mlp.push_back(w->g_mlp[l]);
   }
@@ -230,6 +246,14 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
   // The residual projections (O, down) are split along K when their N is too narrow to fill the
   // chip; the partial products are added to the residual stream by the norm kernel that follows.
   const int so = gemm_residual_splits(T, d, c.n_q_heads * c.head_dim), sd = gemm_residual_splits(T, d, c.d_ffn);
+  // one projection: bf16 weights, or packed 4-bit weights with their group scales
+  auto project = [&](const bf16 *a, const bf16 *wt, const bf16 *scale, void *out, int N, int K, int epi, int splits,
+                     int part) {
+    if (!m->w4) return launch_gemm(a, wt, out, T, N, K, epi, st, splits, part);
+    if (part == GEMM_PART_SMALL) return (arb_status)ARB_OK;            // the 4-bit kernel is one launch
+    return launch_gemm_w4(a, (const uint32_t *)wt, scale, out, T, N, K, epi, st, splits);
+  };
+  auto scale_of = [&](const std::vector<const bf16 *> &v, int l) { return m->w4 ? v[l] : (const bf16 *)nullptr; };
   int pending = 0;
   arb_status s;
   if ((s = launch_token_meta(bt->prefix_lens, bt->cu_step_lens, bt->block_tables, B, T, bt->max_blocks_per_seq,
@@ -248,7 +272,7 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_QKV, st);
-      s = launch_gemm(w.x, m->wqkv[l], w.qkv, T, m->qkv_rows(), d, ARB_EPI_STORE_BF16, st);
+      s = project(w.x, m->wqkv[l], scale_of(m->sqkv, l), w.qkv, m->qkv_rows(), d, ARB_EPI_STORE_BF16, 1, GEMM_PART_ALL);
     }
     if (s) return s;
     {
@@ -266,8 +290,8 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_OPROJ, st);
-      s = launch_gemm(w.attn, m->wo[l], so > 1 ? w.parts : w.h, T, d, c.n_q_heads * c.head_dim, ARB_EPI_RESIDUAL_F32,
-                      st, so);
+      s = project(w.attn, m->wo[l], scale_of(m->so, l), so > 1 ? w.parts : w.h, d, c.n_q_heads * c.head_dim,
+                  ARB_EPI_RESIDUAL_F32, so, GEMM_PART_ALL);
       pending = so > 1 ? so : 0;
     }
     if (s) return s;
@@ -277,14 +301,15 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
       TraceScope t(m, ARB_STAGE_GATE_UP, st);
       {
         TraceScope large(m, ARB_STAGE_GATE_UP_LARGE, st);
-        s = launch_gemm(w.x, m->wgu[l], w.act, T, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, st, 1, GEMM_PART_LARGE);
+        s = project(w.x, m->wgu[l], scale_of(m->sgu, l), w.act, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, 1, GEMM_PART_LARGE);
       }
-      if (!s) s = launch_gemm(w.x, m->wgu[l], w.act, T, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, st, 1, GEMM_PART_SMALL);
+      if (!s) s = project(w.x, m->wgu[l], scale_of(m->sgu, l), w.act, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, 1, GEMM_PART_SMALL);
     }
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_DOWN, st);
-      s = launch_gemm(w.act, m->wd[l], sd > 1 ? w.parts : w.h, T, d, c.d_ffn, ARB_EPI_RESIDUAL_F32, st, sd);
+      s = project(w.act, m->wd[l], scale_of(m->sd, l), sd > 1 ? w.parts : w.h, d, c.d_ffn, ARB_EPI_RESIDUAL_F32, sd,
+                  GEMM_PART_ALL);
       pending = sd > 1 ? sd : 0;
     }
     if (s) return s;
@@ -393,6 +418,20 @@ extern "C" arb_status arb_stage_gemm(const void *A, const void *B, void *C, int3
   if (M == 0) return ARB_OK;
   if (!A || !B || !C) return arb_fail(ARB_EINVAL, "arb_stage_gemm: null pointer");
   return launch_gemm((const bf16 *)A, (const bf16 *)B, C, M, N, K, epilogue, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_w4_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream) {
+  if (N == 0) return ARB_OK;
+  if (!W || !packed || !scales) return arb_fail(ARB_EINVAL, "arb_w4_quantize: null pointer");
+  return launch_w4_quantize((const bf16 *)W, N, K, (uint32_t *)packed, (bf16 *)scales, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_stage_gemm_w4(const void *A, const void *packed, const void *scales, void *C, int32_t M,
+                                        int32_t N, int32_t K, int32_t epilogue, void *stream) {
+  if (M == 0) return ARB_OK;
+  if (!A || !packed || !scales || !C) return arb_fail(ARB_EINVAL, "arb_stage_gemm_w4: null pointer");
+  return launch_gemm_w4((const bf16 *)A, (const uint32_t *)packed, (const bf16 *)scales, C, M, N, K, epilogue,
+                        (hipStream_t)stream);
 }
 
 extern "C" int32_t arb_gemm_large_tile_columns(int32_t M, int32_t N, int32_t K, int32_t epilogue) {

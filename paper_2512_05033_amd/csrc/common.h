@@ -38,6 +38,29 @@ arb_status arb_fail(arb_status st, const char *fmt, ...);
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// ---- tile order shared by the GEMM kernels ----
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give
+// every XCD a contiguous range of logical tiles so that the m-tiles that share a
+// weight tile run on the same L2.
+static __device__ __forceinline__ int xcd_remap(int bid, int total) {
+  const int per = total / 8, rem = total % 8;
+  const int xcd = bid % 8, j = bid / 8;
+  // XCDs [0, rem) hold per+1 tiles, the rest hold per
+  const int base = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+  return base + j;
+}
+
+// Logical tile index -> (tile_m, tile_n): m-tiles in groups of 8, n fastest across groups, so that the
+// tiles an XCD runs at the same time form a compact block (few distinct A and B tiles for its L2).
+static __device__ __forceinline__ void tile_of(int logical, int tiles_m, int tiles_n, int &tile_m, int &tile_n) {
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n, g = logical / per_group, idx = logical - g * per_group;
+  const int rows = min(GM, tiles_m - g * GM);
+  tile_n = idx / rows;
+  tile_m = g * GM + (idx - tile_n * rows);
+}
+
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
 
 // gemm.hip
@@ -92,3 +115,8 @@ arb_status launch_sample_token(const float *logits, int n, int V, float temperat
                                int32_t *token, float *chosen, hipStream_t st);
 arb_status launch_first_stop(const int32_t *tokens, int n, int S, int sep, int eos, int32_t *len, uint8_t *ended,
                              hipStream_t st);
+
+// gemm_w4.hip: 4-bit weights (offset-binary nibbles, eight k per uint32, bf16 scale per row and 128 k)
+arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, hipStream_t st);
+arb_status launch_gemm_w4(const bf16 *A, const uint32_t *Bq, const bf16 *Bscale, void *C, int M, int N, int K,
+                          int epilogue, hipStream_t st, int splits = 1);

@@ -22,27 +22,6 @@ constexpr int LDS_TILE = BM * BK;   // elements per operand tile
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give
-// every XCD a contiguous range of logical tiles so that the m-tiles that share a
-// weight tile run on the same L2.
-__device__ __forceinline__ int xcd_remap(int bid, int total) {
-  const int per = total / 8, rem = total % 8;
-  const int xcd = bid % 8, j = bid / 8;
-  // XCDs [0, rem) hold per+1 tiles, the rest hold per
-  const int base = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-  return base + j;
-}
-
-// Logical tile index -> (tile_m, tile_n): m-tiles in groups of 8, n fastest across groups, so that the
-// tiles an XCD runs at the same time form a compact block (few distinct A and B tiles for its L2).
-__device__ __forceinline__ void tile_of(int logical, int tiles_m, int tiles_n, int &tile_m, int &tile_n) {
-  constexpr int GM = 8;
-  const int per_group = GM * tiles_n, g = logical / per_group, idx = logical - g * per_group;
-  const int rows = min(GM, tiles_m - g * GM);
-  tile_n = idx / rows;
-  tile_m = g * GM + (idx - tile_n * rows);
-}
-
 __device__ __forceinline__ int lds_off(int row, int chunk) {   // element offset of a 16-byte chunk
   return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }

@@ -1,0 +1,272 @@
+// Projection GEMM with 4-bit weights and bf16 activations (the weight-quantized draft of the
+// self-draft regime, Section 5.1): C[M,N] = A[M,K] * W'[N,K]^T with
+// W'[n,k] = q[n,k] * scale[n, k/128], q in [-8, 7] stored as offset-binary nibbles, eight
+// consecutive k per uint32, scale bf16.
+//
+// Structure of the 128x128x64 bf16 kernel (4 waves of 64x64, double-buffered LDS, A by direct-to-LDS
+// loads), except for the weight operand: each thread fetches 16 bytes of packed weights (32 nibbles of
+// one row) one step ahead into registers, expands them to the bf16 integers -8..7 (exact) and stores
+// them into the LDS stage.  The MFMAs therefore accumulate sum_k a[m,k] q[n,k] per group of 128 k
+// (two steps) into a temporary accumulator; at the end of a group it is folded into the result with
+// one fp32 multiply by the group's scale.  No product q*scale is ever rounded to bf16, so the result
+// differs from the definition only by fp32 accumulation.  Weight traffic is a quarter of the bf16
+// kernel's, which is what the small-M (decode) case is bound by.
+#include "common.h"
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 64, GROUP = 128;
+constexpr int LDS_TILE = BM * BK;
+
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+__device__ __forceinline__ int lds_off(int row, int chunk) {   // element offset of a 16-byte chunk, 128-byte rows
+  return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
+}
+
+// eight nibbles (k ascending from the least significant) -> the bf16 integers nibble - 8
+__device__ __forceinline__ bf16x8 expand_nibbles(uint32_t w) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    // 2^23 + nibble as a float, minus (2^23 + 8): exact
+    const float f = __uint_as_float(0x4B000000u | ((w >> (4 * e)) & 15u)) - 8388616.0f;
+    o[e] = (bf16)f;
+  }
+  return o;
+}
+
+__global__ __launch_bounds__(256) void w4_quantize_kernel(const bf16 *__restrict__ W, int N, int K,
+                                                          uint32_t *__restrict__ packed, bf16 *__restrict__ scales) {
+  // 16 threads per group of 128 weights, 8 weights (one word) each
+  const int groups_per_row = K / GROUP;
+  const long long gid = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int l16 = threadIdx.x & 15;
+  if (gid >= (long long)N * groups_per_row) return;
+  const int n = (int)(gid / groups_per_row), g = (int)(gid - (long long)n * groups_per_row);
+  const bf16x8 w = *(const bf16x8 *)(W + (size_t)n * K + g * GROUP + l16 * 8);
+  float m = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf((float)w[e]));
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 16));
+  const bf16 scale = (bf16)(m / 7.0f);
+  const float sf = (float)scale;
+  uint32_t word = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float q = sf == 0.f ? 0.f : rintf((float)w[e] / sf);
+    q = fminf(fmaxf(q, -8.f), 7.f);
+    word |= (uint32_t)((int)q + 8) << (4 * e);
+  }
+  packed[(size_t)n * (K / 8) + g * 16 + l16] = word;
+  if (l16 == 0) scales[gid] = scale;
+}
+
+constexpr int EPI_PARTIAL_F32 = ARB_EPI_STORE_F32;   // in a split-K launch split s stores to C + s*M*N
+
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict__ A, const uint32_t *__restrict__ Bq,
+                                                      const bf16 *__restrict__ Bscale, void *__restrict__ Cv, int M,
+                                                      int N, int K, int tiles_m, int tiles_n) {
+  __shared__ __attribute__((aligned(16))) bf16 As0[LDS_TILE], As1[LDS_TILE], Bs0[LDS_TILE], Bs1[LDS_TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM;
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+
+  // weight row of tile-local B row r.  SwiGLU: wave column r/64, MFMA tile (r%64)/32 (0 = gate, 1 = up),
+  // feature offset r%32; N = F there and the up rows follow the F gate rows.
+  auto weight_row = [&](int r) {
+    if (EPI == ARB_EPI_SWIGLU_BF16) {
+      const int f = tile_n * 64 + (r >> 6) * 32 + (r & 31);
+      return ((r >> 5) & 1) ? N + f : f;
+    }
+    return tile_n * BN + r;
+  };
+
+  // A: four 16-byte chunks per thread and step, by direct-to-LDS loads (swizzle on the global side)
+  const bf16 *a_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, chunk = (c & 7) ^ ((row >> 1) & 7);
+    int am = m0 + row;
+    am = am < M ? am : M - 1;                       // tail rows re-read the last row; never stored
+    a_src[i] = A + (size_t)am * K + chunk * 8;
+  }
+  // B: 32 nibbles (16 bytes) of tile row tid/2 per thread and step
+  const int b_row = tid >> 1, b_half = tid & 1;
+  const uint32_t *bq_src = Bq + (size_t)weight_row(b_row) * (K / 8) + b_half * 4;
+  // scales of this lane's two output column tiles
+  const bf16 *sc_src[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) sc_src[j] = Bscale + (size_t)weight_row(wn * 64 + j * 32 + frag_row) * (K / GROUP);
+
+  f32x16 acc[2][2], tmp[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = tmp[i][j][r] = 0.f;
+
+  // K range of this workgroup in whole groups (two steps each)
+  const int ng_all = K / GROUP;
+  const int g_begin = (int)((long long)ng_all * blockIdx.y / gridDim.y);
+  const int ng = (int)((long long)ng_all * (blockIdx.y + 1) / gridDim.y) - g_begin;
+  const int nk = 2 * ng, last = nk - 1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_src[i] += (size_t)g_begin * GROUP;
+  bq_src += (size_t)g_begin * (GROUP / 8);
+
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma_a = [&](int buf, int kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * BK), LDS_PTR((buf ? As1 : As0) + (i * 4 + wave_u) * 512), 16, 0, 0);
+  };
+  auto load_b = [&](int kt) { return *(const u32x4 *)(bq_src + (size_t)kt * (BK / 8)); };
+  auto store_b = [&](int buf, u32x4 w) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) *(bf16x8 *)&(buf ? Bs1 : Bs0)[lds_off(b_row, b_half * 4 + c)] = expand_nibbles(w[c]);
+  };
+  auto compute = [&](int buf) {
+    bf16x8 fa[2][2], fb[2][2];
+    auto frags = [&](int slot, int kk) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[slot][i] = *(const bf16x8 *)&(buf ? As1 : As0)[lds_off(wm * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
+        fb[slot][i] = *(const bf16x8 *)&(buf ? Bs1 : Bs0)[lds_off(wn * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
+      }
+    };
+    frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      if (kk + 1 < BK / 16) frags((kk + 1) & 1, kk + 1);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          tmp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], tmp[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // Step kt is multiplied out of stage kt%2 while the A tile of step kt+1 streams into the other stage
+  // and the packed weights of step kt+2 are on their way to registers; the weights of step kt+1 are
+  // expanded into the other stage after the MFMAs of step kt.  Steps come in pairs (one group).
+  dma_a(0, 0);
+  u32x4 bw = load_b(0);
+  store_b(0, bw);
+  bw = load_b(min(1, last));
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt += 2) {
+    const int g = g_begin + (kt >> 1);
+    const float sc0 = (float)sc_src[0][g], sc1 = (float)sc_src[1][g];
+    dma_a(1, kt + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(0);
+    store_b(1, bw);
+    bw = load_b(min(kt + 2, last));
+    __syncthreads();
+    dma_a(0, min(kt + 2, last));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(1);
+    store_b(0, bw);
+    bw = load_b(min(kt + 3, last));
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc[i][0][r] = fmaf(tmp[i][0][r], sc0, acc[i][0][r]);
+        acc[i][1][r] = fmaf(tmp[i][1][r], sc1, acc[i][1][r]);
+        tmp[i][0][r] = 0.f;
+        tmp[i][1][r] = 0.f;
+      }
+    __syncthreads();
+  }
+
+  // D layout of the 32x32 MFMA: lane holds column lane%32 and rows 8*(r/4) + 4*(lane/32) + r%4.
+  if (EPI == ARB_EPI_SWIGLU_BF16) {
+    bf16 *C = (bf16 *)Cv;
+    const int col = tile_n * 64 + wn * 32 + frag_row;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        if (m < M) {
+          const float gte = acc[i][0][r], up = acc[i][1][r];
+          C[(size_t)m * N + col] = (bf16)(gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up);
+        }
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = tile_n * BN + wn * 64 + j * 32 + frag_row;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+          if (m < M) {
+            if (EPI == ARB_EPI_STORE_BF16) {
+              ((bf16 *)Cv)[(size_t)m * N + col] = (bf16)acc[i][j][r];
+            } else if (EPI == EPI_PARTIAL_F32) {
+              ((float *)Cv)[((size_t)blockIdx.y * M + m) * N + col] = acc[i][j][r];
+            } else {
+              float *dst = (float *)Cv + (size_t)m * N + col;
+              *dst += acc[i][j][r];
+            }
+          }
+        }
+      }
+  }
+}
+
+}  // namespace
+
+arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, hipStream_t st) {
+  if (N == 0) return ARB_OK;
+  if (N < 0 || K <= 0 || K % GROUP != 0) return arb_fail(ARB_EUNSUPPORTED, "w4_quantize: N=%d, K=%d (K must be a multiple of %d)", N, K, GROUP);
+  const long long groups = (long long)N * (K / GROUP);
+  hipLaunchKernelGGL(w4_quantize_kernel, dim3((unsigned)((groups + 15) / 16)), dim3(256), 0, st, W, N, K, packed, scales);
+  ARB_CHECK_LAUNCH("w4_quantize");
+  return ARB_OK;
+}
+
+arb_status launch_gemm_w4(const bf16 *A, const uint32_t *Bq, const bf16 *Bscale, void *C, int M, int N, int K,
+                          int epilogue, hipStream_t st, int splits) {
+  if (M == 0) return ARB_OK;
+  if (M < 0 || N <= 0 || K <= 0) return arb_fail(ARB_EINVAL, "gemm_w4: M=%d N=%d K=%d", M, N, K);
+  if (K % GROUP != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm_w4: K=%d is not a multiple of %d", K, GROUP);
+  const int tiles_m = ceil_div(M, BM);
+  int tiles_n;
+  if (epilogue == ARB_EPI_SWIGLU_BF16) {
+    if (N % 64 != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm_w4: SwiGLU width %d is not a multiple of 64", N);
+    tiles_n = N / 64;
+  } else {
+    if (N % BN != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm_w4: N=%d is not a multiple of %d", N, BN);
+    tiles_n = N / BN;
+  }
+  if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32) return arb_fail(ARB_EINVAL, "gemm_w4: split-K needs the residual epilogue");
+  if (splits < 1 || splits > K / GROUP) return arb_fail(ARB_EINVAL, "gemm_w4: %d splits of %d groups", splits, K / GROUP);
+  const dim3 grid(tiles_m * tiles_n, splits), block(256);
+#define ARB_W4(E) hipLaunchKernelGGL((gemm_w4_kernel<E>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K, tiles_m, tiles_n)
+  switch (epilogue) {
+    case ARB_EPI_STORE_BF16: ARB_W4(ARB_EPI_STORE_BF16); break;
+    case ARB_EPI_RESIDUAL_F32:
+      if (splits > 1) ARB_W4(EPI_PARTIAL_F32); else ARB_W4(ARB_EPI_RESIDUAL_F32);
+      break;
+    case ARB_EPI_SWIGLU_BF16: ARB_W4(ARB_EPI_SWIGLU_BF16); break;
+    case ARB_EPI_STORE_F32: ARB_W4(ARB_EPI_STORE_F32); break;
+    default: return arb_fail(ARB_EINVAL, "gemm_w4: unknown epilogue %d", epilogue);
+  }
+#undef ARB_W4
+  ARB_CHECK_LAUNCH("gemm_w4");
+  return ARB_OK;
+}

@@ -529,6 +529,70 @@ def test_empty_batch_and_bad_arguments(A):
     assert err.value.status == A.ARB_ECAPACITY
 
 
+# ------------------------------------------------------------- 4-bit draft weights
+
+def _packed_np(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("N,K", [(128, 128), (300, 1536), (2048, 8960)])
+def test_w4_quantize_bit_exact(A, N, K):
+    w = rand_bf16((N, K), 0.02, 51)
+    w[1, :128] = 0                                                          # a group of zeros
+    w[2, 5] = 3.0                                                           # an outlier that sets its group's scale
+    packed, scales = A.arb_w4_quantize(w)
+    q, sb = O.w4_quantize(W.bf16_bits(w))
+    assert np.array_equal(W.bf16_bits(scales), sb)
+    assert np.array_equal(_packed_np(packed), O.w4_pack(q))
+
+
+@pytest.mark.parametrize("M,N,K,epi", [(1, 128, 128, "store"), (16, 1536, 8960, "f32"), (200, 2048, 1536, "store"),
+                                       (130, 8960, 1536, "swiglu"), (333, 1536, 1536, "residual"),
+                                       (1024, 4480, 1536, "swiglu")])
+def test_w4_gemm(A, M, N, K, epi):
+    rows = 2 * N if epi == "swiglu" else N
+    a, w = rand_bf16((M, K), 1.0, 52), rand_bf16((rows, K), 0.05, 53)
+    packed, scales = A.arb_w4_quantize(w)
+    q, sb = O.w4_quantize(W.bf16_bits(w))
+    ref = bf16_np(a) @ O.w4_dequantize(q, sb).T                             # the definition: dequantize, then multiply
+    if epi == "store":
+        got = bf16_np(A.arb_stage_gemm_w4(a, packed, scales, A.ARB_EPI_STORE_BF16))
+        assert rel_err(got, ref) < 4e-3
+    elif epi == "f32":
+        got = A.arb_stage_gemm_w4(a, packed, scales, A.ARB_EPI_STORE_F32).cpu().numpy()
+        assert rel_err(got, ref) < 1e-5
+    elif epi == "residual":
+        h0 = torch.randn(M, N, device="cuda")
+        h = h0.clone()
+        A.arb_stage_gemm_w4(a, packed, scales, A.ARB_EPI_RESIDUAL_F32, out=h)
+        assert rel_err(h.cpu().numpy(), h0.cpu().numpy().astype(np.float64) + ref) < 1e-5
+    else:
+        got = bf16_np(A.arb_stage_gemm_w4(a, packed, scales, A.ARB_EPI_SWIGLU_BF16))
+        assert got.shape == (M, N) and rel_err(got, O.silu(ref[:, :N]) * ref[:, N:]) < 5e-3
+
+
+def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A):
+    """The whole forward with 4-bit projection weights (C2's shape, 2 layers, so that split-K, SwiGLU
+    and the plain epilogue all run on packed weights) against the oracle given the dequantized values."""
+    w = W.scaled(W.C2, n_layers=2, batch=4)
+    batch = W.make_batch(w)
+    weights = W.make_weights(w.model, w.seed, "cuda", gain_jitter=0.1)
+    qw = A.QuantizedWeights(weights)
+    model = H().make_model(w.model, qw)
+    ks, vs = W.make_kv_pools(w, batch, "cuda")
+    kv, db = A.KVCache(ks, vs), H().device_batch(batch)
+    scores, esc, hidden = A.arb_score_steps(model, kv, db, batch.tau, want_hidden=True)
+    # the oracle's parameters: every projection replaced by its dequantized values (float64 arrays)
+    p = oracle_params(W.make_weights(w.model, w.seed, "cpu", gain_jitter=0.1))
+    for name in ("wqkv", "wo", "wgu", "wd"):
+        setattr(p, name, [O.w4_dequantize(*O.w4_quantize(bits)) for bits in getattr(p, name)])
+    kp, vp = oracle_pools(*W.make_kv_pools(w, batch, "cpu"))
+    s_ref, e_ref, y_ref = O.score_steps(oracle_model(w.model), p, kp, vp, batch.token_ids, batch.prefix_lens,
+                                        batch.cu_step_lens, batch.block_tables, batch.tau)
+    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+    _assert_scores(batch, scores, esc, s_ref, e_ref)
+
+
 # ------------------------------------------------------------------ Algorithm 1 loop
 
 def _tiny_role(A, name, seed, n_blocks, with_lm):

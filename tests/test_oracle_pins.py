@@ -563,6 +563,33 @@ def test_arbitrage_inference_follows_algorithm_1():
     assert O.arbitrage_inference([7, EOS], draft, router, target, 0.5, EOS, 5) == ([7, EOS], [])
 
 
+def test_w4_quantization_definition():
+    r = np.random.default_rng(12)
+    w = O.float_to_bf16(r.normal(0, 0.02, (6, 384)))
+    w[2, 128:256] = 0                                                    # a group of zeros: scale 0, q 0
+    q, sb = O.w4_quantize(w)
+    wf, s = O.bf16_to_float(w), O.bf16_to_float(sb)
+    assert q.dtype == np.int8 and q.min() >= -8 and q.max() <= 7 and sb.shape == (6, 3)
+    assert np.all(q[2, 128:256] == 0) and s[2, 1] == 0
+    wd = O.w4_dequantize(q, sb)
+    g = lambda a: a.reshape(6, 3, 128)
+    # the scale is max|w|/7 to bf16 precision; the error of an unclipped entry is at most half a step
+    assert np.allclose(s, np.abs(g(wf)).max(2) / 7, rtol=2 ** -8)
+    unclipped = np.abs(g(wf)) <= 7 * s[:, :, None]
+    assert np.all(np.abs(g(wd) - g(wf))[unclipped] <= 0.5 * np.repeat(s[:, :, None], 128, 2)[unclipped] * (1 + 1e-6))
+    # the largest entry of a group lands on +-7 (or +-8 where the bf16 rounding of the scale went down)
+    big = np.abs(g(q)).max(2)
+    assert np.all((big[s > 0] == 7) | (big[s > 0] == 8))
+    # integers times the scale are fixed points
+    again, sb2 = O.w4_quantize(O.float_to_bf16(7 * np.repeat(s, 128, 1) * np.sign(r.normal(size=(6, 384)))))
+    assert np.array_equal(sb2, sb) and np.all(np.abs(again[np.repeat(s, 128, 1) > 0]) == 7)
+    # packing: nibble j of word i is q[8i + j] + 8
+    p = O.w4_pack(q)
+    assert p.dtype == np.uint32 and p.shape == (6, 48)
+    for (n, k) in ((0, 0), (3, 77), (5, 383)):
+        assert (int(p[n, k // 8]) >> (4 * (k % 8))) & 15 == int(q[n, k]) + 8
+
+
 # ----------------------------------------------------------------------- stored values
 
 def _golden(name):
