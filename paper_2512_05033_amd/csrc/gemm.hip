@@ -177,6 +177,199 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
 }
 
 // ---------------------------------------------------------------------------------------------
+// Deep-ring variant of the 128x128 tile for launches of at most one workgroup per CU (narrow
+// projections, remainders).  Such a launch is bound by memory latency: a CU only has the loads of
+// its one workgroup in flight.  K steps of 32 through a ring of 8 LDS stages (128 KB) keep seven
+// steps in flight instead of one.  LDS rows are 64 bytes here; chunks are swizzled by row/4.
+constexpr int RK = 32, RING_STAGES = 8;
+constexpr int RING_STAGE_ELEMS = (BM + BN) * RK;   // A rows then B rows
+
+__device__ __forceinline__ int lds_off32(int row, int chunk) {   // element offset of a 16-byte chunk, 64-byte rows
+  return row * 32 + ((chunk ^ ((row >> 2) & 3)) << 3);
+}
+
+// s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, lgkmcnt in 11:8, expcnt 6:4 left at "no wait")
+constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70; }
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
+                                                   void *__restrict__ Cv, int M, int N, int K, int tiles_m,
+                                                   int tiles_n, int tile_n0) {
+  // one array per stage (the compiler orders LDS reads against in-flight loads by object)
+  __shared__ __attribute__((aligned(16))) bf16 St0[RING_STAGE_ELEMS], St1[RING_STAGE_ELEMS], St2[RING_STAGE_ELEMS],
+      St3[RING_STAGE_ELEMS], St4[RING_STAGE_ELEMS], St5[RING_STAGE_ELEMS], St6[RING_STAGE_ELEMS], St7[RING_STAGE_ELEMS];
+#define ARB_ST(s) ((s) == 0 ? St0 : (s) == 1 ? St1 : (s) == 2 ? St2 : (s) == 3 ? St3 : (s) == 4 ? St4 : (s) == 5 ? St5 : (s) == 6 ? St6 : St7)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  tile_n += tile_n0;                 // this launch covers n-tiles [tile_n0, tile_n0 + tiles_n)
+  const int m0 = tile_m * BM;
+
+  // This thread's two 16-byte chunks per operand and step: tile rows tid/4 + 64 i, the same chunk for
+  // both (the swizzle term (row/4)%4 does not depend on i).
+  const int row0 = tid >> 2, chunk = (tid & 3) ^ ((row0 >> 2) & 3);
+  const bf16 *a_src[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    int am = m0 + row0 + 64 * i;
+    am = am < M ? am : M - 1;                       // tail rows re-read the last row; never stored
+    a_src[i] = A + (size_t)am * K + chunk * 8;
+  }
+  // B rows of chunk i are b_row0 + i * (rows per i).  For SwiGLU the tile-local row r maps to wave column
+  // r/64, MFMA tile (r%64)/32 (0 = gate, 1 = up) and feature offset r%32, i.e. feature
+  // tile_n*64 + (r/64)*32 + r%32 of the gate or up half; N = F there.
+  const int b_row0 = EPI == ARB_EPI_SWIGLU_BF16 ? tile_n * 64 + (row0 & 31) + ((row0 >> 5) & 1) * N : tile_n * BN + row0;
+  const size_t b_step = (size_t)(EPI == ARB_EPI_SWIGLU_BF16 ? 32 : 64) * K;
+  const bf16 *b_src = B + (size_t)b_row0 * K + chunk * 8;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // K range of this workgroup (the whole of K unless the launch is split along K)
+  const int nk_all = K / RK;
+  const int kt_begin = (int)((long long)nk_all * blockIdx.y / gridDim.y);
+  const int nk = (int)((long long)nk_all * (blockIdx.y + 1) / gridDim.y) - kt_begin, last = nk - 1;
+  a_src[0] += (size_t)kt_begin * RK;
+  a_src[1] += (size_t)kt_begin * RK;
+  b_src += (size_t)kt_begin * RK;
+
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma_a = [&](int s, int kt) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + (i * 4 + wave_u) * 512), 16, 0, 0);
+  };
+  auto dma_b = [&](int s, int kt) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src + i * b_step + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + BM * RK + (i * 4 + wave_u) * 512), 16, 0, 0);
+  };
+  // The swizzle term of a fragment row depends on frag_row only, so each operand needs one LDS offset
+  // per sub-step; MFMA tile and stage are constant displacements from it.
+  const int a_off[2] = {lds_off32(wm * 64 + frag_row, frag_half), lds_off32(wm * 64 + frag_row, 2 + frag_half)};
+  const int b_off[2] = {BM * RK + lds_off32(wn * 64 + frag_row, frag_half),
+                        BM * RK + lds_off32(wn * 64 + frag_row, 2 + frag_half)};
+  bf16x8 fa[2][2], fb[2][2];
+  auto frags = [&](int slot, int s, int kk) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      fa[slot][i] = *(const bf16x8 *)&ARB_ST(s)[a_off[kk] + i * 32 * RK];
+      fb[slot][i] = *(const bf16x8 *)&ARB_ST(s)[b_off[kk] + i * 32 * RK];
+    }
+  };
+  auto mfmas = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+  };
+  // Step out of stage s (two sub-steps of 4 MFMAs); on entry fragment slot 0 holds its first sub-step.
+  // `refill` is the step loaded into the stage before s, which every wave left at the previous barrier
+  // (clamped to the last step past the end; those copies are never read).  Before the barrier this
+  // wave's reads of stage s have returned and its loads of the next step have landed: they are the
+  // oldest of its loads in flight, the 4 * (RING_STAGES - 3) + 2 issued since may stay in flight.  (A full
+  // workgroup fence would wait for all of them.)
+  auto step = [&](int s, int refill) {
+    const int prev = (s + RING_STAGES - 1) % RING_STAGES, next = (s + 1) % RING_STAGES;
+    frags(1, s, 1);
+    dma_a(prev, refill);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (RING_STAGES - 3) + 2));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    frags(0, next, 0);
+    dma_b(prev, refill);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // The same without a refill, for the steps after the last whole turn of the ring: nothing is loaded
+  // any more, so the wait is for everything still in flight.
+  auto drain_step = [&](int s) {
+    frags(1, s, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    frags(0, (s + 1) % RING_STAGES, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+#pragma unroll
+  for (int s = 0; s < RING_STAGES - 1; ++s) {
+    dma_a(s, min(s, last));
+    dma_b(s, min(s, last));
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (RING_STAGES - 2)));   // step 0 has landed
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  frags(0, 0, 0);
+  // Whole turns of the ring in a branch-free body, then the 0..RING_STAGES-1 steps that are left.
+  int kt = 0;
+  for (; kt + RING_STAGES <= nk; kt += RING_STAGES) {
+#pragma unroll
+    for (int s = 0; s < RING_STAGES; ++s) step(s, min(kt + s + RING_STAGES - 1, last));
+  }
+  const int rem = nk - kt;
+#pragma unroll
+  for (int s = 0; s < RING_STAGES - 1; ++s)
+    if (s < rem) drain_step(s);
+#undef ARB_ST
+
+  // D layout of the 32x32 MFMA: lane holds column lane%32 and rows 8*(r/4) + 4*(lane/32) + r%4.
+  if (EPI == ARB_EPI_SWIGLU_BF16) {
+    bf16 *C = (bf16 *)Cv;
+    const int col = tile_n * 64 + wn * 32 + frag_row;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        if (m < M) {
+          const float gte = acc[i][0][r], up = acc[i][1][r];
+          C[(size_t)m * N + col] = (bf16)(gte / (1.0f + __expf(-gte)) * up);
+        }
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = tile_n * BN + wn * 64 + j * 32 + frag_row;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+          if (m < M) {
+            if (EPI == ARB_EPI_STORE_BF16) {
+              ((bf16 *)Cv)[(size_t)m * N + col] = (bf16)acc[i][j][r];
+            } else if (EPI == EPI_PARTIAL_F32) {
+              ((float *)Cv)[((size_t)blockIdx.y * M + m) * N + col] = acc[i][j][r];
+            } else {
+              float *dst = (float *)Cv + (size_t)m * N + col;
+              *dst += acc[i][j][r];
+            }
+          }
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Large-tile variant for launches that fill the chip with 256x256 tiles.  Global->LDS traffic
 // per flop halves against the 128x128 tile (a CU's vector-memory path moves ~50-60 bytes/clock,
 // which caps the small tile at about half the MFMA rate), and a fragment read (1 KB per wave)
@@ -194,9 +387,6 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
 constexpr int LM = 256, LN = 256, LK = 32;
 constexpr int L_TILE = LM * LK;          // elements per operand and stage
 
-__device__ __forceinline__ int lds_off32(int row, int chunk) {
-  return row * LK + ((chunk ^ ((row >> 2) & 3)) << 3);
-}
 
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
@@ -426,7 +616,14 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   tiles_n -= tile_n0;
   if (tiles_n == 0 || part == GEMM_PART_LARGE) return ARB_OK;
   const dim3 grid(tiles_m * tiles_n, splits), block(256);
-#define ARB_SMALL(E) hipLaunchKernelGGL((gemm_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0)
+  const bool ring = tiles_m * tiles_n * splits <= 256;      // at most one workgroup per CU: latency-bound
+#define ARB_SMALL(E)                                                                                              \
+  do {                                                                                                            \
+    if (ring)                                                                                                     \
+      hipLaunchKernelGGL((gemm_ring_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0); \
+    else                                                                                                          \
+      hipLaunchKernelGGL((gemm_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0);      \
+  } while (0)
   switch (epilogue) {
     case ARB_EPI_STORE_BF16: ARB_SMALL(ARB_EPI_STORE_BF16); break;
     case ARB_EPI_RESIDUAL_F32:
