@@ -246,6 +246,14 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
   // The residual projections (O, down) are split along K when their N is too narrow to fill the
   // chip; the partial products are added to the residual stream by the norm kernel that follows.
   const int so = gemm_residual_splits(T, d, c.n_q_heads * c.head_dim), sd = gemm_residual_splits(T, d, c.d_ffn);
+  // The QKV projection is narrow as well; when its tiles leave half the CUs idle it is split along K
+  // into fp32 partial products (in `parts`, free at that point) that rope_append adds up, which also
+  // spares q and k a rounding.
+  int sq = 256 / (ceil_div(T, 128) * (m->qkv_rows() / 128));
+  if (sq > d / 256) sq = d / 256;
+  if (sq > 8 * d / m->qkv_rows()) sq = 8 * d / m->qkv_rows();
+  if (sq > 4) sq = 4;
+  if (sq < 2) sq = 1;
   // one projection: bf16 weights, or packed 4-bit weights with their group scales
   auto project = [&](const bf16 *a, const bf16 *wt, const bf16 *scale, void *out, int N, int K, int epi, int splits,
                      int part) {
@@ -272,12 +280,15 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_QKV, st);
-      s = project(w.x, m->wqkv[l], scale_of(m->sqkv, l), w.qkv, m->qkv_rows(), d, ARB_EPI_STORE_BF16, 1, GEMM_PART_ALL);
+      if (sq > 1)
+        s = project(w.x, m->wqkv[l], scale_of(m->sqkv, l), w.parts, m->qkv_rows(), d, ARB_EPI_STORE_F32, sq, GEMM_PART_ALL);
+      else
+        s = project(w.x, m->wqkv[l], scale_of(m->sqkv, l), w.qkv, m->qkv_rows(), d, ARB_EPI_STORE_BF16, 1, GEMM_PART_ALL);
     }
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_ROPE_APPEND, st);
-      s = launch_rope_append(w.qkv, w.cs, w.tok_slot, (bf16 *)kv->k_pool[l], (bf16 *)kv->v_pool[l], T, c.n_q_heads,
+      s = launch_rope_append(w.qkv, w.parts, sq > 1 ? sq : 0, w.cs, w.tok_slot, (bf16 *)kv->k_pool[l], (bf16 *)kv->v_pool[l], T, c.n_q_heads,
                              c.n_kv_heads, c.head_dim, st);
     }
     if (s) return s;
@@ -485,7 +496,7 @@ extern "C" arb_status arb_stage_rope_append(const arb_model *m, void *qkv, void 
                              batch->max_blocks_per_seq, c.kv_block, tok_pos, tok_slot, st)))
     return s;
   if ((s = launch_rope_table(tok_pos, (int)T, c.head_dim, c.rope_base, cs, st))) return s;
-  return launch_rope_append((bf16 *)qkv, cs, tok_slot, (bf16 *)k_pool, (bf16 *)v_pool, (int)T, c.n_q_heads,
+  return launch_rope_append((bf16 *)qkv, nullptr, 0, cs, tok_slot, (bf16 *)k_pool, (bf16 *)v_pool, (int)T, c.n_q_heads,
                             c.n_kv_heads, c.head_dim, st);
 }
 

@@ -64,8 +64,9 @@ static __device__ __forceinline__ void tile_of(int logical, int tiles_m, int til
 // ---- launchers implemented in the kernel files (all asynchronous on `st`) ----
 
 // gemm.hip
-// With splits > 1 (residual epilogue only) C is not accumulated into: split s writes its fp32 partial
-// product to C + s*M*N and the consumer adds the partials to the residual stream (see the norm kernels).
+// With splits > 1 (residual and fp32-store epilogues) C is not accumulated into: split s writes its fp32
+// partial product to C + s*M*N and the consumer adds the partials up (the norm kernels for the residual
+// stream, rope_append for q/k/v).
 // A launch is up to two kernels: n-tile columns [0, gemm_large_cols) in 256x256 tiles, the rest in
 // 128x128 tiles; `part` restricts the call to one of them.
 enum { GEMM_PART_ALL = 0, GEMM_PART_LARGE = 1, GEMM_PART_SMALL = 2 };
@@ -100,8 +101,11 @@ arb_status launch_embed_rmsnorm(const bf16 *embed, const int32_t *token_ids, con
 // parts/n_parts: fp32 partial products [n_parts, T, d] that are first added to h (and h is updated).
 arb_status launch_rmsnorm(float *h, const float *parts, int n_parts, const float *g, float eps, int T, int d, bf16 *x,
                           hipStream_t st);
-arb_status launch_rope_append(bf16 *qkv, const f32x2 *cs, const int32_t *tok_slot, bf16 *k_pool, bf16 *v_pool, int T,
-                              int n_q_heads, int n_kv_heads, int head_dim, hipStream_t st);
+// parts/n_parts: when n_parts > 0 the projection is read as the sum of fp32 partial products
+// [n_parts, T, (Hq+2Hkv)*hd] instead of from qkv; the rotated q is written to qkv (bf16) either way.
+arb_status launch_rope_append(bf16 *qkv, const float *parts, int n_parts, const f32x2 *cs, const int32_t *tok_slot,
+                              bf16 *k_pool, bf16 *v_pool, int T, int n_q_heads, int n_kv_heads, int head_dim,
+                              hipStream_t st);
 arb_status launch_final_norm_head(const float *h, const float *parts, int n_parts, const float *g, float eps, int T,
                                   int d, const float *w_head, bf16 *hidden_out, float *tok_dot, hipStream_t st);
 arb_status launch_pool_route(const float *tok_dot, const int32_t *cu_step_lens, int batch, float b_head, int pool,

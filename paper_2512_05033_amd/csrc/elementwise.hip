@@ -207,28 +207,46 @@ arb_status launch_final_norm_head(const float *h, const float *parts, int n_part
 // One block per token.  A work unit is (head, two adjacent pair indices t, t+1):
 // it reads u[t..t+1] and u[t+half..t+half+1] of that head, rotates q and k heads
 // by the token's table row ((a, b) -> (a cos - b sin, b cos + a sin)), writes q
-// back in place and k, v (bf16) to the token's slot of the pool
-// [n_blocks, Hkv, 16, hd].
-__global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv, const f32x2 *__restrict__ cs,
+// (bf16) to the qkv row and k, v (bf16) to the token's slot of the pool
+// [n_blocks, Hkv, 16, hd].  With PARTS the projection comes as fp32 split-K partial
+// products that are added up here (fixed order), so q and k are rounded once.
+template <bool PARTS>
+__global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv, const float *__restrict__ parts,
+                                                          int n_parts, size_t part_stride,
+                                                          const f32x2 *__restrict__ cs,
                                                           const int32_t *__restrict__ tok_slot,
                                                           bf16 *__restrict__ k_pool, bf16 *__restrict__ v_pool,
                                                           int Hq, int Hkv, int hd) {
   const int j = blockIdx.x;
   const int half = hd / 2, units_per_head = half / 2, n_heads = Hq + 2 * Hkv;
   bf16 *row = qkv + (size_t)j * n_heads * hd;
+  const float *prow = PARTS ? parts + (size_t)j * n_heads * hd : nullptr;
   const int slot = tok_slot[j];
   const size_t blk = slot / ARB_KV_BLOCK, off = slot % ARB_KV_BLOCK;
   for (int u = threadIdx.x; u < n_heads * units_per_head; u += blockDim.x) {
     const int head = u / units_per_head, t = (u - head * units_per_head) * 2;
     bf16 *src = row + head * hd;
-    const bf16x2 a = *(const bf16x2 *)(src + t), b = *(const bf16x2 *)(src + t + half);
-    bf16x2 oa = a, ob = b;
+    float a[2], b[2];
+    if (PARTS) {
+      a[0] = a[1] = b[0] = b[1] = 0.f;
+      for (int p = 0; p < n_parts; ++p) {
+        const float *ps = prow + p * part_stride + head * hd;
+        const f32x2 pa = *(const f32x2 *)(ps + t), pb = *(const f32x2 *)(ps + t + half);
+        a[0] += pa[0]; a[1] += pa[1]; b[0] += pb[0]; b[1] += pb[1];
+      }
+    } else {
+      const bf16x2 va = *(const bf16x2 *)(src + t), vb = *(const bf16x2 *)(src + t + half);
+      a[0] = (float)va[0]; a[1] = (float)va[1]; b[0] = (float)vb[0]; b[1] = (float)vb[1];
+    }
+    bf16x2 oa, ob;
     if (head < Hq + Hkv) {
       const f32x2 cs0 = cs[(size_t)j * half + t], cs1 = cs[(size_t)j * half + t + 1];
-      oa[0] = (bf16)((float)a[0] * cs0[0] - (float)b[0] * cs0[1]);
-      ob[0] = (bf16)((float)b[0] * cs0[0] + (float)a[0] * cs0[1]);
-      oa[1] = (bf16)((float)a[1] * cs1[0] - (float)b[1] * cs1[1]);
-      ob[1] = (bf16)((float)b[1] * cs1[0] + (float)a[1] * cs1[1]);
+      oa[0] = (bf16)(a[0] * cs0[0] - b[0] * cs0[1]);
+      ob[0] = (bf16)(b[0] * cs0[0] + a[0] * cs0[1]);
+      oa[1] = (bf16)(a[1] * cs1[0] - b[1] * cs1[1]);
+      ob[1] = (bf16)(b[1] * cs1[0] + a[1] * cs1[1]);
+    } else {
+      oa[0] = (bf16)a[0]; oa[1] = (bf16)a[1]; ob[0] = (bf16)b[0]; ob[1] = (bf16)b[1];
     }
     bf16 *dst;
     if (head < Hq) {
@@ -243,11 +261,17 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv
   }
 }
 
-arb_status launch_rope_append(bf16 *qkv, const f32x2 *cs, const int32_t *tok_slot, bf16 *k_pool, bf16 *v_pool, int T,
-                              int n_q_heads, int n_kv_heads, int head_dim, hipStream_t st) {
+arb_status launch_rope_append(bf16 *qkv, const float *parts, int n_parts, const f32x2 *cs, const int32_t *tok_slot,
+                              bf16 *k_pool, bf16 *v_pool, int T, int n_q_heads, int n_kv_heads, int head_dim,
+                              hipStream_t st) {
   if (T == 0) return ARB_OK;
-  hipLaunchKernelGGL(rope_append_kernel, dim3(T), dim3(256), 0, st, qkv, cs, tok_slot, k_pool, v_pool, n_q_heads,
-                     n_kv_heads, head_dim);
+  const size_t stride = (size_t)T * (n_q_heads + 2 * n_kv_heads) * head_dim;
+  if (n_parts > 0)
+    hipLaunchKernelGGL((rope_append_kernel<true>), dim3(T), dim3(256), 0, st, qkv, parts, n_parts, stride, cs, tok_slot,
+                       k_pool, v_pool, n_q_heads, n_kv_heads, head_dim);
+  else
+    hipLaunchKernelGGL((rope_append_kernel<false>), dim3(T), dim3(256), 0, st, qkv, (const float *)nullptr, 0, stride, cs,
+                       tok_slot, k_pool, v_pool, n_q_heads, n_kv_heads, head_dim);
   ARB_CHECK_LAUNCH("rope_append");
   return ARB_OK;
 }

@@ -595,7 +595,8 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
     if (N % BN != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm: N=%d is not a multiple of %d", N, BN);
     tiles_n = N / BN;
   }
-  if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32) return arb_fail(ARB_EINVAL, "gemm: split-K needs the residual epilogue");
+  if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32 && epilogue != ARB_EPI_STORE_F32)
+    return arb_fail(ARB_EINVAL, "gemm: split-K needs an fp32 epilogue (partial products)");
   if (splits < 1 || splits > K / BK) return arb_fail(ARB_EINVAL, "gemm: %d splits of %d K-steps", splits, K / BK);
   const int big_cols = gemm_large_cols(M, N, K, epilogue, splits);   // n-tile columns given to the large-tile kernel
   if (big_cols > 0 && part != GEMM_PART_SMALL) {

@@ -253,7 +253,8 @@ arb_status launch_gemm_w4(const bf16 *A, const uint32_t *Bq, const bf16 *Bscale,
     if (N % BN != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm_w4: N=%d is not a multiple of %d", N, BN);
     tiles_n = N / BN;
   }
-  if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32) return arb_fail(ARB_EINVAL, "gemm_w4: split-K needs the residual epilogue");
+  if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32 && epilogue != ARB_EPI_STORE_F32)
+    return arb_fail(ARB_EINVAL, "gemm_w4: split-K needs an fp32 epilogue (partial products)");
   if (splits < 1 || splits > K / GROUP) return arb_fail(ARB_EINVAL, "gemm_w4: %d splits of %d groups", splits, K / GROUP);
   const dim3 grid(tiles_m * tiles_n, splits), block(256);
 #define ARB_W4(E) hipLaunchKernelGGL((gemm_w4_kernel<E>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K, tiles_m, tiles_n)
