@@ -181,8 +181,9 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
 // projections, remainders).  Such a launch is bound by memory latency: a CU only has the loads of
 // its one workgroup in flight.  K steps of 32 through a ring of 8 LDS stages (128 KB) keep seven
 // steps in flight instead of one.  LDS rows are 64 bytes here; chunks are swizzled by row/4.
+// MI = 32-row MFMA tiles per wave along M: 2 gives the 128x128 tile, 1 a 64x128 tile for launches
+// that would otherwise leave more than half of the CUs without a workgroup.
 constexpr int RK = 32, RING_STAGES = 8;
-constexpr int RING_STAGE_ELEMS = (BM + BN) * RK;   // A rows then B rows
 
 __device__ __forceinline__ int lds_off32(int row, int chunk) {   // element offset of a 16-byte chunk, 64-byte rows
   return row * 32 + ((chunk ^ ((row >> 2) & 3)) << 3);
@@ -191,10 +192,13 @@ __device__ __forceinline__ int lds_off32(int row, int chunk) {   // element offs
 // s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, lgkmcnt in 11:8, expcnt 6:4 left at "no wait")
 constexpr int waitcnt_vm_lgkm0(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70; }
 
-template <int EPI>
+template <int EPI, int MI>
 __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                    void *__restrict__ Cv, int M, int N, int K, int tiles_m,
                                                    int tiles_n, int tile_n0) {
+  constexpr int RBM = 64 * MI;                              // rows of the tile
+  constexpr int RING_STAGE_ELEMS = (RBM + BN) * RK;         // A rows then B rows
+  constexpr int LOADS = MI + 2;                             // wave-wide loads per wave and step
   // one array per stage (the compiler orders LDS reads against in-flight loads by object)
   __shared__ __attribute__((aligned(16))) bf16 St0[RING_STAGE_ELEMS], St1[RING_STAGE_ELEMS], St2[RING_STAGE_ELEMS],
       St3[RING_STAGE_ELEMS], St4[RING_STAGE_ELEMS], St5[RING_STAGE_ELEMS], St6[RING_STAGE_ELEMS], St7[RING_STAGE_ELEMS];
@@ -205,14 +209,14 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   int tile_m, tile_n;
   tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
   tile_n += tile_n0;                 // this launch covers n-tiles [tile_n0, tile_n0 + tiles_n)
-  const int m0 = tile_m * BM;
+  const int m0 = tile_m * RBM;
 
-  // This thread's two 16-byte chunks per operand and step: tile rows tid/4 + 64 i, the same chunk for
-  // both (the swizzle term (row/4)%4 does not depend on i).
+  // This thread's 16-byte chunks per step: tile rows tid/4 + 64 i of A (i < MI) and of B (i < 2), the
+  // same chunk for all (the swizzle term (row/4)%4 does not depend on i).
   const int row0 = tid >> 2, chunk = (tid & 3) ^ ((row0 >> 2) & 3);
-  const bf16 *a_src[2];
+  const bf16 *a_src[MI];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < MI; ++i) {
     int am = m0 + row0 + 64 * i;
     am = am < M ? am : M - 1;                       // tail rows re-read the last row; never stored
     a_src[i] = A + (size_t)am * K + chunk * 8;
@@ -224,9 +228,9 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   const size_t b_step = (size_t)(EPI == ARB_EPI_SWIGLU_BF16 ? 32 : 64) * K;
   const bf16 *b_src = B + (size_t)b_row0 * K + chunk * 8;
 
-  f32x16 acc[2][2];
+  f32x16 acc[MI][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -236,47 +240,46 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   const int nk_all = K / RK;
   const int kt_begin = (int)((long long)nk_all * blockIdx.y / gridDim.y);
   const int nk = (int)((long long)nk_all * (blockIdx.y + 1) / gridDim.y) - kt_begin, last = nk - 1;
-  a_src[0] += (size_t)kt_begin * RK;
-  a_src[1] += (size_t)kt_begin * RK;
+#pragma unroll
+  for (int i = 0; i < MI; ++i) a_src[i] += (size_t)kt_begin * RK;
   b_src += (size_t)kt_begin * RK;
 
   const int frag_row = lane & 31, frag_half = lane >> 5;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto dma_a = [&](int s, int kt) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + (i * 4 + wave_u) * 512), 16, 0, 0);
   };
   auto dma_b = [&](int s, int kt) {
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src + i * b_step + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + BM * RK + (i * 4 + wave_u) * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src + i * b_step + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + RBM * RK + (i * 4 + wave_u) * 512), 16, 0, 0);
   };
   // The swizzle term of a fragment row depends on frag_row only, so each operand needs one LDS offset
   // per sub-step; MFMA tile and stage are constant displacements from it.
-  const int a_off[2] = {lds_off32(wm * 64 + frag_row, frag_half), lds_off32(wm * 64 + frag_row, 2 + frag_half)};
-  const int b_off[2] = {BM * RK + lds_off32(wn * 64 + frag_row, frag_half),
-                        BM * RK + lds_off32(wn * 64 + frag_row, 2 + frag_half)};
-  bf16x8 fa[2][2], fb[2][2];
+  const int a_off[2] = {lds_off32(wm * 32 * MI + frag_row, frag_half), lds_off32(wm * 32 * MI + frag_row, 2 + frag_half)};
+  const int b_off[2] = {RBM * RK + lds_off32(wn * 64 + frag_row, frag_half),
+                        RBM * RK + lds_off32(wn * 64 + frag_row, 2 + frag_half)};
+  bf16x8 fa[2][MI], fb[2][2];
   auto frags = [&](int slot, int s, int kk) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      fa[slot][i] = *(const bf16x8 *)&ARB_ST(s)[a_off[kk] + i * 32 * RK];
-      fb[slot][i] = *(const bf16x8 *)&ARB_ST(s)[b_off[kk] + i * 32 * RK];
-    }
+    for (int i = 0; i < MI; ++i) fa[slot][i] = *(const bf16x8 *)&ARB_ST(s)[a_off[kk] + i * 32 * RK];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) fb[slot][j] = *(const bf16x8 *)&ARB_ST(s)[b_off[kk] + j * 32 * RK];
   };
   auto mfmas = [&](int slot) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
   };
-  // Step out of stage s (two sub-steps of 4 MFMAs); on entry fragment slot 0 holds its first sub-step.
+  // Step out of stage s (two sub-steps of 2 MI MFMAs); on entry fragment slot 0 holds its first sub-step.
   // `refill` is the step loaded into the stage before s, which every wave left at the previous barrier
   // (clamped to the last step past the end; those copies are never read).  Before the barrier this
   // wave's reads of stage s have returned and its loads of the next step have landed: they are the
-  // oldest of its loads in flight, the 4 * (RING_STAGES - 3) + 2 issued since may stay in flight.  (A full
+  // oldest of its loads in flight, the LOADS * (RING_STAGES - 3) + MI issued since may stay in flight.  (A full
   // workgroup fence would wait for all of them.)
   auto step = [&](int s, int refill) {
     const int prev = (s + RING_STAGES - 1) % RING_STAGES, next = (s + 1) % RING_STAGES;
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
     __builtin_amdgcn_sched_barrier(0);
     mfmas(0);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (RING_STAGES - 3) + 2));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LOADS * (RING_STAGES - 3) + MI));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     frags(0, next, 0);
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
     dma_a(s, min(s, last));
     dma_b(s, min(s, last));
   }
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(4 * (RING_STAGES - 2)));   // step 0 has landed
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LOADS * (RING_STAGES - 2)));   // step 0 has landed
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_sched_barrier(0);
   frags(0, 0, 0);
@@ -336,24 +339,24 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
     bf16 *C = (bf16 *)Cv;
     const int col = tile_n * 64 + wn * 32 + frag_row;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        const int m = m0 + wm * 32 * MI + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
         if (m < M) {
           const float gte = acc[i][0][r], up = acc[i][1][r];
-          C[(size_t)m * N + col] = (bf16)(gte / (1.0f + __expf(-gte)) * up);
+          C[(size_t)m * N + col] = (bf16)(gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up);
         }
       }
   } else {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int col = tile_n * BN + wn * 64 + j * 32 + frag_row;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+          const int m = m0 + wm * 32 * MI + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
           if (m < M) {
             if (EPI == ARB_EPI_STORE_BF16) {
               ((bf16 *)Cv)[(size_t)m * N + col] = (bf16)acc[i][j][r];
@@ -616,14 +619,19 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   const int tile_n0 = big_cols * 2;                   // small n-tiles covered by the large-tile launch
   tiles_n -= tile_n0;
   if (tiles_n == 0 || part == GEMM_PART_LARGE) return ARB_OK;
-  const dim3 grid(tiles_m * tiles_n, splits), block(256);
+  const dim3 block(256);
   const bool ring = tiles_m * tiles_n * splits <= 256;      // at most one workgroup per CU: latency-bound
-#define ARB_SMALL(E)                                                                                              \
-  do {                                                                                                            \
-    if (ring)                                                                                                     \
-      hipLaunchKernelGGL((gemm_ring_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0); \
-    else                                                                                                          \
-      hipLaunchKernelGGL((gemm_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0);      \
+  const bool half = tiles_m * tiles_n * splits <= 128;      // not even half of the CUs: 64-row tiles
+  const int tm64 = ceil_div(M, 64);
+  const dim3 grid(tiles_m * tiles_n, splits), grid64(tm64 * tiles_n, splits);
+#define ARB_SMALL(E)                                                                                                  \
+  do {                                                                                                                \
+    if (half)                                                                                                         \
+      hipLaunchKernelGGL((gemm_ring_kernel<E, 1>), grid64, block, 0, st, A, B, C, M, N, K, tm64, tiles_n, tile_n0);   \
+    else if (ring)                                                                                                    \
+      hipLaunchKernelGGL((gemm_ring_kernel<E, 2>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0);  \
+    else                                                                                                              \
+      hipLaunchKernelGGL((gemm_kernel<E>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0);          \
   } while (0)
   switch (epilogue) {
     case ARB_EPI_STORE_BF16: ARB_SMALL(ARB_EPI_STORE_BF16); break;
