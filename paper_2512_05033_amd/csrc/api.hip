@@ -244,7 +244,9 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
   const AttnPlan plan = plan_attention(B, bt->prefix_lens_host, bt->cu_step_lens_host, G, c.n_kv_heads);
 
   // The residual projections (O, down) are split along K when their N is too narrow to fill the
-  // chip; the partial products are added to the residual stream by the norm kernel that follows.
+  // chip; their fp32 products (one per split; a single one when not split: a plain store is cheaper
+  // in the GEMM epilogue than a read-modify-write of the stream) are added to the residual stream by
+  // the norm kernel that follows.
   const int so = gemm_residual_splits(T, d, c.n_q_heads * c.head_dim), sd = gemm_residual_splits(T, d, c.d_ffn);
   // The QKV projection is narrow as well; when its tiles leave half the CUs idle it is split along K
   // into fp32 partial products (in `parts`, free at that point) that rope_append adds up, which also
@@ -301,9 +303,9 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_OPROJ, st);
-      s = project(w.attn, m->wo[l], scale_of(m->so, l), so > 1 ? w.parts : w.h, d, c.n_q_heads * c.head_dim,
-                  ARB_EPI_RESIDUAL_F32, so, GEMM_PART_ALL);
-      pending = so > 1 ? so : 0;
+      s = project(w.attn, m->wo[l], scale_of(m->so, l), w.parts, d, c.n_q_heads * c.head_dim,
+                  so > 1 ? ARB_EPI_RESIDUAL_F32 : ARB_EPI_STORE_F32, so, GEMM_PART_ALL);
+      pending = so;
     }
     if (s) return s;
     if ((s = launch_rmsnorm(w.h, w.parts, pending, m->g_mlp[l], c.rms_eps, T, d, w.x, st))) return s;
@@ -319,9 +321,9 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_DOWN, st);
-      s = project(w.act, m->wd[l], scale_of(m->sd, l), sd > 1 ? w.parts : w.h, d, c.d_ffn, ARB_EPI_RESIDUAL_F32, sd,
-                  GEMM_PART_ALL);
-      pending = sd > 1 ? sd : 0;
+      s = project(w.act, m->wd[l], scale_of(m->sd, l), w.parts, d, c.d_ffn,
+                  sd > 1 ? ARB_EPI_RESIDUAL_F32 : ARB_EPI_STORE_F32, sd, GEMM_PART_ALL);
+      pending = sd;
     }
     if (s) return s;
   }
