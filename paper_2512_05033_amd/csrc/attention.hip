@@ -4,7 +4,7 @@
 // that share hk and the s_b step tokens form s_b*G query rows (row = i*G + g,
 // token-major).  A workgroup of 4 waves takes 128 rows (32 per wave) and one
 // chunk of the key range ("split"); chunks of a sequence are merged afterwards
-// from their online-softmax states (m, l, unnormalised acc).  Every KV byte is
+// from their online-softmax states (m, l) and normalised partial results (bf16).  Every KV byte is
 // streamed from HBM once per 128 rows that need it; rows of different query
 // tiles of the same (b, hk) meet in L2.
 //
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
     const bf16 *__restrict__ q, int q_row_stride, const bf16 *__restrict__ k_pool, const bf16 *__restrict__ v_pool,
     const int32_t *__restrict__ block_tables, int max_blocks, const int32_t *__restrict__ prefix_lens,
     const int32_t *__restrict__ cu, int T, int Hq, int Hkv, int max_qtiles, int max_splits, int kv_chunk,
-    float scale_log2, bf16 *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml) {
+    float scale_log2, bf16 *__restrict__ out, bf16 *__restrict__ part_acc, float *__restrict__ part_ml) {
   constexpr int CPK = HD / 8;              // 16-byte chunks per key
   constexpr int LOADS = KT * CPK / 256;    // wave-wide 1 KB loads per wave, operand and tile
   constexpr int KPL = 64 / CPK;            // keys covered by one wave-wide load (4 or 8: inside one block)
@@ -272,13 +272,19 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
         *(bf16x4 *)(dst + mt * 32 + 8 * r4 + 4 * half) = v;
       }
   } else {
-    float *dst = part_acc + ((size_t)split * T * Hq + orow) * HD;
+    // the split's own normalised result in bf16 (it lies in the hull of the values, like the output)
+    // plus its (m, l) in fp32: half the partial traffic of fp32 accumulators
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    bf16 *dst = part_acc + ((size_t)split * T * Hq + orow) * HD;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-        *(f32x4 *)(dst + mt * 32 + 8 * r4 + 4 * half) =
-            f32x4{o[mt][r4 * 4], o[mt][r4 * 4 + 1], o[mt][r4 * 4 + 2], o[mt][r4 * 4 + 3]};
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[mt][r4 * 4 + e] * inv);
+        *(bf16x4 *)(dst + mt * 32 + 8 * r4 + 4 * half) = v;
+      }
     if (half == 0) {
       float *ml = part_ml + ((size_t)split * T * Hq + orow) * 2;
       ml[0] = m_run;
@@ -287,36 +293,41 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
   }
 }
 
-// Merge of the split partials: out = sum_s w_s acc_s / sum_s w_s l_s with
-// w_s = exp2(m_s - max_s m_s).  One wave per (token, head).
+// Merge of the split partials: out = sum_s w_s l_s o_s / sum_s w_s l_s with
+// w_s = exp2(m_s - max_s m_s) and o_s the split's normalised result.  A thread owns eight
+// consecutive elements of one (token, head) row, so a workgroup of 256 merges 2048 / HD rows.
 template <int HD>
-__global__ __launch_bounds__(64) void attention_merge_kernel(const float *__restrict__ part_acc,
-                                                             const float *__restrict__ part_ml,
-                                                             const int32_t *__restrict__ tok_pos, int T, int Hq,
-                                                             int kv_chunk, bf16 *__restrict__ out) {
-  const int idx = blockIdx.x;             // token * Hq + head
-  const int tok = idx / Hq;
-  const int n_splits = tok_pos[tok] / kv_chunk + 1;      // splits that start at or before this token's position
+__global__ __launch_bounds__(256) void attention_merge_kernel(const bf16 *__restrict__ part_acc,
+                                                              const float *__restrict__ part_ml,
+                                                              const int32_t *__restrict__ tok_pos, int T, int Hq,
+                                                              int kv_chunk, bf16 *__restrict__ out) {
+  constexpr int TPR = HD / 8;                              // threads per row
   const size_t stride = (size_t)T * Hq;
-  float m = -INFINITY;
-  for (int sidx = 0; sidx < n_splits; ++sidx) m = fmaxf(m, part_ml[(sidx * stride + idx) * 2]);
-  constexpr int PER = HD / 64;
-  float acc[PER];
+  const size_t idx = (size_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;      // token * Hq + head
+  if (idx >= stride) return;
+  const int piece = threadIdx.x % TPR;
+  const int n_splits = tok_pos[idx / Hq] / kv_chunk + 1;   // splits that start at or before this token's position
+  float m = -INFINITY, l = 0.f;
+  float acc[8];
 #pragma unroll
-  for (int e = 0; e < PER; ++e) acc[e] = 0.f;
-  float l = 0.f;
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll 2
   for (int sidx = 0; sidx < n_splits; ++sidx) {
-    const float ms = part_ml[(sidx * stride + idx) * 2];
-    if (ms == -INFINITY) continue;
-    const float w = exp2f(ms - m);
-    l += w * part_ml[(sidx * stride + idx) * 2 + 1];
-    const float *src = part_acc + (sidx * stride + idx) * HD + threadIdx.x * PER;
+    const float2 ml = *(const float2 *)(part_ml + (sidx * stride + idx) * 2);
+    const bf16x8 v = *(const bf16x8 *)(part_acc + (sidx * stride + idx) * HD + piece * 8);
+    if (ml.x == -INFINITY) continue;                       // no key of this split is visible to the row
+    const float m_new = fmaxf(m, ml.x);
+    const float keep = exp2f(m - m_new), w = exp2f(ml.x - m_new) * ml.y;
+    m = m_new;
+    l = l * keep + w;
 #pragma unroll
-    for (int e = 0; e < PER; ++e) acc[e] += w * src[e];
+    for (int e = 0; e < 8; ++e) acc[e] = acc[e] * keep + w * (float)v[e];
   }
   const float inv = 1.0f / l;
+  bf16x8 r;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) out[(size_t)idx * HD + threadIdx.x * PER + e] = (bf16)(acc[e] * inv);
+  for (int e = 0; e < 8; ++e) r[e] = (bf16)(acc[e] * inv);
+  *(bf16x8 *)(out + idx * HD + piece * 8) = r;
 }
 
 }  // namespace
@@ -355,7 +366,7 @@ AttnPlan plan_attention(int batch, const int32_t *prefix_host, const int32_t *cu
 
 size_t attention_ws_bytes(int max_splits_cap, int total_tokens, int n_q_heads, int head_dim) {
   const size_t rows = (size_t)max_splits_cap * total_tokens * n_q_heads;
-  return align_up(rows * head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256) +
+  return align_up(rows * head_dim * sizeof(bf16), 256) + align_up(rows * 2 * sizeof(float), 256) +
          align_up((size_t)total_tokens * sizeof(int32_t), 256);
 }
 
@@ -367,7 +378,8 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
   if (batch == 0 || total_tokens == 0) return ARB_OK;
   if (head_dim != 64 && head_dim != 128) return arb_fail(ARB_EUNSUPPORTED, "attention: head_dim %d", head_dim);
   const bool split = plan.max_splits > 1;
-  float *part_acc = nullptr, *part_ml = nullptr;
+  bf16 *part_acc = nullptr;
+  float *part_ml = nullptr;
   const int32_t *tok_pos = tok_pos_in;      // position of every step token; computed here when not given
   if (split) {
     const size_t need = attention_ws_bytes(plan.max_splits, total_tokens, n_q_heads, head_dim);
@@ -375,7 +387,7 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
       return arb_fail(ARB_ECAPACITY, "attention: workspace %zu < %zu bytes", ws_bytes, need);
     const size_t rows = (size_t)plan.max_splits * total_tokens * n_q_heads;
     char *pws = (char *)ws;
-    part_acc = (float *)pws; pws += align_up(rows * head_dim * sizeof(float), 256);
+    part_acc = (bf16 *)pws; pws += align_up(rows * head_dim * sizeof(bf16), 256);
     part_ml = (float *)pws;  pws += align_up(rows * 2 * sizeof(float), 256);
     if (!tok_pos) {
       tok_pos = (int32_t *)pws;
@@ -395,7 +407,7 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
 #undef ARB_ATTN_LAUNCH
   ARB_CHECK_LAUNCH("attention");
   if (split) {
-    const dim3 mgrid(total_tokens * n_q_heads), mblock(64);
+    const dim3 mgrid(ceil_div(total_tokens * n_q_heads, 2048 / head_dim)), mblock(256);
     if (head_dim == 128)
       hipLaunchKernelGGL((attention_merge_kernel<128>), mgrid, mblock, 0, st, part_acc, part_ml, tok_pos, total_tokens,
                          n_q_heads, plan.kv_chunk, out);
