@@ -29,6 +29,7 @@ namespace {
 
 constexpr int QROWS = 128;     // query rows per workgroup
 constexpr int KT = 64;         // keys per tile
+constexpr float kLazyLog2 = 8.0f;   // growth of a row maximum (log2 units) that forces a rescale
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
@@ -86,10 +87,13 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[t][r]);
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  // The reference maximum m_run is advanced only when some row's maximum has outgrown it by more
+  // than kLazyLog2: until then exp2(s - m_run) <= 2^kLazyLog2, far inside the range of bf16 and
+  // fp32, and o / l is unchanged because both carry the same factor.  Most tiles then skip the
+  // rescaling of the accumulators.
   const float m_new = fmaxf(m_run, mx * scale_log2);
-  const float m_use = m_new == -INFINITY ? 0.f : m_new;
-  if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {     // some row's max moved: rescale the state
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
+  if (__builtin_amdgcn_ballot_w64(m_new > m_run + kLazyLog2) != 0) {     // also the first visible key (m_run = -inf)
+    const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));   // m_run = -inf -> 0
     l_run *= alpha;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -97,6 +101,7 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
       for (int r = 0; r < 16; ++r) o[mt][r] *= alpha;
     m_run = m_new;
   }
+  const float m_use = m_run == -INFINITY ? 0.f : m_run;
   float l_add = 0.f;
   bf16x8 pf[2][2];
 #pragma unroll
@@ -213,24 +218,33 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
   const int n_tiles = (kv_end - kv_begin + KT - 1) / KT;
   const int lkey = lane / CPK, pchunk = lane % CPK;
   int blk_id[LOADS];                       // pool block of each load of the tile to be issued next
+  const unsigned first_blk = (unsigned)kv_begin / ARB_KV_BLOCK + (unsigned)(wave_u * KPL) / ARB_KV_BLOCK;
   auto lookup = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int key0 = kv_begin + tile * KT + (i * 4 + wave_u) * KPL;
-      blk_id[i] = table[min(key0 / ARB_KV_BLOCK, last_blk)];
+      const unsigned blk = first_blk + (unsigned)(tile * KT + i * 4 * KPL) / ARB_KV_BLOCK;
+      blk_id[i] = table[min(blk, (unsigned)last_blk)];
     }
   };
+  // Lane-constant part of the addresses: load i of a tile covers keys [wave*KPL, wave*KPL + KPL) of the
+  // tile's 16-key block i*KPL/4 + wave*KPL/16, so the key inside its block and the swizzled chunk do not
+  // depend on i or on the tile; only the (scalar) pool block does.
+  const int kib = (wave_u * KPL + lkey) % ARB_KV_BLOCK;
+  const int swz = HD == 128 ? kib : (((wave_u * KPL + lkey) >> 1) & 7);
+  const unsigned voff = (unsigned)(kib * HD + ((pchunk ^ swz) << 3)) * 2u;                                 // bytes
+  const unsigned voff_tail = (unsigned)(min(kib, last_key % ARB_KV_BLOCK) * HD + ((pchunk ^ swz) << 3)) * 2u;
+  const char *k_head = (const char *)(k_pool + (size_t)hk * ARB_KV_BLOCK * HD);
+  const char *v_head = (const char *)(v_pool + (size_t)hk * ARB_KV_BLOCK * HD);
+  const unsigned blk_bytes = (unsigned)Hkv * ARB_KV_BLOCK * HD * 2u;
   auto dma = [&](bf16 *dk, bf16 *dv, int tile) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int g = i * 4 + wave_u;                                  // 1 KB slot of the tile
-      const int tkey = g * KPL + lkey;                               // tile-local key of this lane
-      const int j = min(kv_begin + tile * KT + tkey, last_key);
-      const int blk = min((kv_begin + tile * KT + g * KPL) / ARB_KV_BLOCK, last_blk);
-      const int chunk = pchunk ^ (HD == 128 ? (tkey & 15) : ((tkey >> 1) & 7));
-      const size_t src = (((size_t)blk_id[i] * Hkv + hk) * ARB_KV_BLOCK + (j - blk * ARB_KV_BLOCK)) * HD + chunk * 8;
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(k_pool + src), LDS_PTR(dk + g * 512), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(v_pool + src), LDS_PTR(dv + g * 512), 16, 0, 0);
+      const unsigned blk = first_blk + (unsigned)(tile * KT + i * 4 * KPL) / ARB_KV_BLOCK;
+      const unsigned off = blk >= (unsigned)last_blk ? voff_tail : voff;       // scalar choice between two lane vectors
+      const uint64_t base = (uint64_t)(unsigned)blk_id[i] * blk_bytes;
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(k_head + base + off), LDS_PTR(dk + g * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(v_head + base + off), LDS_PTR(dv + g * 512), 16, 0, 0);
     }
   };
 
