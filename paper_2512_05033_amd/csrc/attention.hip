@@ -36,12 +36,26 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
+// Chunk swizzles.  A key row of a stage is HD/8 chunks of 16 bytes; chunk c of key k sits in slot
+// c ^ swizzle(k).  The LDS has 64 banks of 4 bytes and serves 256 bytes per clock:
+//  - K is read with ds_read_b128, 16 lanes (16 consecutive keys, one chunk) per clock: the slots of
+//    16 consecutive keys must cover 256 bytes, so with 256-byte rows the swizzle is k mod 16, with
+//    128-byte rows (two keys per 256 bytes) it is (k/2) mod 8;
+//  - V is read with ds_read_b64_tr_b16, 32 lanes (4 consecutive keys x 4 consecutive chunks) per
+//    clock: the two low key bits must move the slot by multiples of 4, so the key bits are rotated
+//    (measured on this access pattern: 171 bytes/clock/CU against 63 with the K swizzle).
 template <int HD>
-__device__ __forceinline__ int kv_off(int key, int chunk) {   // element offset of a 16-byte chunk of a key row
-  // 16 lanes (256 bytes = all banks) are served together: with 256-byte rows the 16 keys need 16
-  // distinct chunk slots, with 128-byte rows 8 slots times the row parity
-  return key * HD + ((chunk ^ (HD == 128 ? (key & 15) : ((key >> 1) & 7))) << 3);
+__device__ __forceinline__ int k_swizzle(int key) { return HD == 128 ? (key & 15) : ((key >> 1) & 7); }
+template <int HD>
+__device__ __forceinline__ int v_swizzle(int key) {
+  if (HD == 128) return ((key & 3) << 2) | ((key >> 2) & 3);
+  const int x = (key >> 1) & 7;                  // 128-byte rows: the row parity picks the 128-byte half
+  return ((x & 1) << 2) | (x >> 1);
 }
+template <int HD>
+__device__ __forceinline__ int k_off(int key, int chunk) { return key * HD + ((chunk ^ k_swizzle<HD>(key)) << 3); }   // elements
+template <int HD>
+__device__ __forceinline__ int v_off(int key, int chunk) { return key * HD + ((chunk ^ v_swizzle<HD>(key)) << 3); }
 
 // One 64-key tile for one wave: scores, online softmax update, O^T accumulation.
 template <int HD>
@@ -58,13 +72,13 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
     // K fragments of step kk+1 are read while the MFMAs of step kk run
     bf16x8 kf[2][2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) kf[0][t] = *(const bf16x8 *)&sk[kv_off<HD>(t * 32 + col, half)];
+    for (int t = 0; t < 2; ++t) kf[0][t] = *(const bf16x8 *)&sk[k_off<HD>(t * 32 + col, half)];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
       if (kk + 1 < KSTEPS) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
-          kf[(kk + 1) & 1][t] = *(const bf16x8 *)&sk[kv_off<HD>(t * 32 + col, (kk + 1) * 2 + half)];
+          kf[(kk + 1) & 1][t] = *(const bf16x8 *)&sk[k_off<HD>(t * 32 + col, (kk + 1) * 2 + half)];
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][t], qf[kk], st[t], 0, 0, 0);
@@ -124,8 +138,8 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int c = mt * 32 + vcol;
-        const bf16 *a0 = &sv[kv_off<HD>(key0, c >> 3) + (c & 7)];
-        const bf16 *a1 = &sv[kv_off<HD>(key0 + 8, c >> 3) + (c & 7)];
+        const bf16 *a0 = &sv[v_off<HD>(key0, c >> 3) + (c & 7)];
+        const bf16 *a1 = &sv[v_off<HD>(key0 + 8, c >> 3) + (c & 7)];
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a0);
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a1);
         union { s16x4 s[2]; bf16x8 b; } vf;
@@ -230,9 +244,11 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
   // tile's 16-key block i*KPL/4 + wave*KPL/16, so the key inside its block and the swizzled chunk do not
   // depend on i or on the tile; only the (scalar) pool block does.
   const int kib = (wave_u * KPL + lkey) % ARB_KV_BLOCK;
-  const int swz = HD == 128 ? kib : (((wave_u * KPL + lkey) >> 1) & 7);
-  const unsigned voff = (unsigned)(kib * HD + ((pchunk ^ swz) << 3)) * 2u;                                 // bytes
-  const unsigned voff_tail = (unsigned)(min(kib, last_key % ARB_KV_BLOCK) * HD + ((pchunk ^ swz) << 3)) * 2u;
+  const int tkey = wave_u * KPL + lkey;            // tile-local key of load 0 (the others differ by multiples of 16 or 32)
+  const unsigned koff = (unsigned)(kib * HD + ((pchunk ^ k_swizzle<HD>(tkey)) << 3)) * 2u;                  // bytes
+  const unsigned voff = (unsigned)(kib * HD + ((pchunk ^ v_swizzle<HD>(tkey)) << 3)) * 2u;
+  const int kib_tail = min(kib, last_key % ARB_KV_BLOCK);
+  const unsigned koff_tail = koff - (unsigned)((kib - kib_tail) * HD) * 2u, voff_tail = voff - (unsigned)((kib - kib_tail) * HD) * 2u;
   const char *k_head = (const char *)(k_pool + (size_t)hk * ARB_KV_BLOCK * HD);
   const char *v_head = (const char *)(v_pool + (size_t)hk * ARB_KV_BLOCK * HD);
   const unsigned blk_bytes = (unsigned)Hkv * ARB_KV_BLOCK * HD * 2u;
@@ -241,10 +257,10 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
     for (int i = 0; i < LOADS; ++i) {
       const int g = i * 4 + wave_u;                                  // 1 KB slot of the tile
       const unsigned blk = first_blk + (unsigned)(tile * KT + i * 4 * KPL) / ARB_KV_BLOCK;
-      const unsigned off = blk >= (unsigned)last_blk ? voff_tail : voff;       // scalar choice between two lane vectors
+      const bool tail = blk >= (unsigned)last_blk;                    // scalar choice between two lane vectors
       const uint64_t base = (uint64_t)(unsigned)blk_id[i] * blk_bytes;
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(k_head + base + off), LDS_PTR(dk + g * 512), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(v_head + base + off), LDS_PTR(dv + g * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(k_head + base + (tail ? koff_tail : koff)), LDS_PTR(dk + g * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(v_head + base + (tail ? voff_tail : voff)), LDS_PTR(dv + g * 512), 16, 0, 0);
     }
   };
 
