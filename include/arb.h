@@ -61,13 +61,21 @@ typedef enum { ARB_POOL_MEAN = 0, ARB_POOL_LAST = 1 } arb_pool_mode;
  * score > tau (Section 3.1).  In both, a NaN score escalates. */
 typedef enum { ARB_ESCALATE_IF_GT = 0, ARB_ACCEPT_IF_GT = 1 } arb_route_sense;
 
+/* The router head (arb_model_cfg.has_router_head).  LINEAR: one fp32 vector w_head [d], the score is the
+ * raw value w_head . pool + b_head (what the workload configs use; tau is a threshold on that scale).
+ * TWO_CLASS: the two-way classification head of Section 4.2 ("Training": class 1 = the target's step has
+ * the higher PRM score): w_head is fp32 [2, d] (row 0 class 0, row 1 class 1), b_head is the bias
+ * difference c_1 - c_0, and the score is the softmax probability of class 1,
+ * y_hat = 1 / (1 + exp(-((w_1 - w_0) . pool + b_head))), so tau is a probability. */
+typedef enum { ARB_HEAD_NONE = 0, ARB_HEAD_LINEAR = 1, ARB_HEAD_TWO_CLASS = 2 } arb_head_kind;
+
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rms_eps;        /* added to the mean square under the root */
   float rope_base;      /* rotary angle of pair t at position pos: pos * base^(-2t/head_dim) */
   int32_t kv_block;     /* tokens per KV block (16) */
   int32_t pool;         /* arb_pool_mode */
-  int32_t has_router_head; /* 0: target pass (hidden states only) */
+  int32_t has_router_head; /* arb_head_kind; 0: target pass (hidden states only) */
 } arb_model_cfg;
 
 /* Weights.  All DEVICE pointers, caller-owned, must outlive the model.  The
@@ -79,8 +87,8 @@ typedef struct {
  *   wo    [d, Hq * hd]
  *   wgu   [2 F, d]                rows: F gate rows, then F up rows; MLP = (silu(x Wg^T) * (x Wu^T)) Wd^T
  *   wd    [d, F]
- * RMSNorm gains g_attn[l], g_mlp[l], g_final are fp32 [d]; w_head is fp32 [d]
- * (NULL when has_router_head == 0); b_head is the head's scalar bias. */
+ * RMSNorm gains g_attn[l], g_mlp[l], g_final are fp32 [d]; w_head is fp32 [d] (fp32 [2, d] for
+ * ARB_HEAD_TWO_CLASS; NULL when has_router_head == 0); b_head is the head's scalar bias. */
 typedef struct {
   const void *embed;
   const void *const *wqkv, *const *wo, *const *wgu, *const *wd;
@@ -134,8 +142,8 @@ size_t arb_workspace_bytes(const arb_model *m, int32_t max_batch, int32_t max_to
 
 /* The router forward (Section 4.2; Alg. 1 "routing decision") or, with
  * has_router_head == 0, the target's pass over an appended step.
- *   scores     device fp32 [batch]: y_hat_b = w_head . pool_b(final-normed hidden) + b_head;
- *              required iff has_router_head, else must be NULL
+ *   scores     device fp32 [batch]: y_hat_b = w_head . pool_b(final-normed hidden) + b_head (the class-1
+ *              probability for ARB_HEAD_TWO_CLASS); required iff has_router_head, else must be NULL
  *   escalate   device uint8 [batch] or NULL: 1 iff not (y_hat_b <= tau)
  *   hidden_out device bf16 [total_tokens, d_model] or NULL: final-normed hidden states
  *   ws         device workspace of ws_bytes >= arb_workspace_bytes(...)

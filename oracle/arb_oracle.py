@@ -266,9 +266,12 @@ def forward(m: Model, w: Params, k_pools: Sequence[np.ndarray], v_pools: Sequenc
 
 
 def router_scores(y: np.ndarray, cu_step_lens, w_head, b_head: float = 0.0, mode: str = "mean") -> np.ndarray:
-    """Linear head on the pooled step hidden states: mean over the step's tokens
-    (the workload configs' reading) or the step's final token (Section 4.2,
-    'Training': head on the final-token embedding)."""
+    """Head on the pooled step hidden states: mean over the step's tokens (the
+    workload configs' reading) or the step's final token (Section 4.2,
+    'Training': head on the final-token embedding).  A [d] head gives the raw
+    linear score.  A [2, d] head is the two-way classification head of Section
+    4.2: logits z_c = w_c . pooled + c_c with (c_0, c_1) = (0, b_head), and the
+    score is the softmax probability of class 1 (the router's y_hat)."""
     w_head = as_float(w_head)
     B = len(cu_step_lens) - 1
     out = np.zeros(B, dtype=F)
@@ -280,7 +283,12 @@ def router_scores(y: np.ndarray, cu_step_lens, w_head, b_head: float = 0.0, mode
             pooled = seg[-1]
         else:
             raise ValueError(mode)
-        out[b] = pooled @ w_head + b_head
+        if w_head.ndim == 2:
+            z = w_head @ pooled + np.array([0.0, b_head], dtype=F)
+            e = np.exp(z - z.max())
+            out[b] = e[1] / e.sum()
+        else:
+            out[b] = pooled @ w_head + b_head
     return out
 
 

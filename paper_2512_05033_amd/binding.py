@@ -18,6 +18,7 @@ _lib = None
 
 ARB_OK, ARB_EINVAL, ARB_ESHAPE, ARB_ECAPACITY, ARB_EHIP, ARB_EUNSUPPORTED = range(6)
 ARB_POOL_MEAN, ARB_POOL_LAST = 0, 1
+ARB_HEAD_NONE, ARB_HEAD_LINEAR, ARB_HEAD_TWO_CLASS = 0, 1, 2
 ARB_ESCALATE_IF_GT, ARB_ACCEPT_IF_GT = 0, 1
 ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16, ARB_EPI_STORE_F32 = 0, 1, 2, 3
 (ARB_STAGE_QKV, ARB_STAGE_ATTENTION, ARB_STAGE_OPROJ, ARB_STAGE_GATE_UP, ARB_STAGE_DOWN, ARB_STAGE_NORM,
@@ -156,10 +157,15 @@ class Model:
         proj = torch.int32 if scales is not None else bf
         self._keep = [_dev(w.embed, bf), *[_dev(t, proj) for l in (w.wqkv, w.wo, w.wgu, w.wd) for t in l],
                       *[_dev(t, f32) for l in (w.g_attn, w.g_mlp) for t in l], _dev(w.g_final, f32)]
+        head_kind = ARB_HEAD_NONE
         if has_router_head:
             self._keep.append(_dev(w.w_head, f32))
+            # a [2, d] head is the two-class head (scores are class-1 probabilities), a [d] head the linear one
+            head_kind = ARB_HEAD_TWO_CLASS if w.w_head.dim() == 2 else ARB_HEAD_LINEAR
+            if tuple(w.w_head.shape) not in ((d_model,), (2, d_model)):
+                raise ValueError(f"w_head has shape {tuple(w.w_head.shape)}")
         self.cfg = _Cfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rms_eps, rope_base,
-                        kv_block, pool, int(has_router_head))
+                        kv_block, pool, head_kind)
         self._arrays = [_ptr_array(l) for l in (w.wqkv, w.wo, w.wgu, w.wd, w.g_attn, w.g_mlp)]
         self._scale_arrays = [None] * 4
         if scales is not None:

@@ -65,6 +65,8 @@ extern "C" arb_status arb_model_create(const arb_model_cfg *cfg, const arb_weigh
     return arb_fail(ARB_EUNSUPPORTED, "arb_model_create: (Hq + 2 Hkv) * head_dim must be a multiple of 128");
   if (!w->embed || !w->wqkv || !w->wo || !w->wgu || !w->wd || !w->g_attn || !w->g_mlp || !w->g_final)
     return arb_fail(ARB_EINVAL, "arb_model_create: null weight pointer");
+  if (c.has_router_head < 0 || c.has_router_head > ARB_HEAD_TWO_CLASS)
+    return arb_fail(ARB_EINVAL, "arb_model_create: has_router_head = %d", c.has_router_head);
   if (c.has_router_head && !w->w_head) return arb_fail(ARB_EINVAL, "arb_model_create: has_router_head but w_head is null");
   for (int l = 0; l < c.n_layers; ++l)
     if (!w->wqkv[l] || !w->wo[l] || !w->wgu[l] || !w->wd[l] || !w->g_attn[l] || !w->g_mlp[l])
@@ -333,11 +335,13 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     ARB_CHECK_HIP(hipMemcpyAsync(h_out, w.h, (size_t)T * d * sizeof(float), hipMemcpyDeviceToDevice, st));
     return ARB_OK;
   }
+  const bool two_class = c.has_router_head == ARB_HEAD_TWO_CLASS;
   if ((s = launch_final_norm_head(w.h, w.parts, pending, m->g_final, c.rms_eps, T, d, with_head ? m->w_head : nullptr,
+                                  with_head && two_class ? m->w_head + d : nullptr,
                                   (bf16 *)hidden_out, with_head ? w.tok_dot : nullptr, st)))
     return s;
   if (with_head)
-    if ((s = launch_pool_route(w.tok_dot, bt->cu_step_lens, B, m->b_head, c.pool, tau, scores, escalate, st))) return s;
+    if ((s = launch_pool_route(w.tok_dot, bt->cu_step_lens, B, m->b_head, c.pool, two_class, tau, scores, escalate, st))) return s;
   return ARB_OK;
 }
 
@@ -525,8 +529,8 @@ extern "C" arb_status arb_stage_norm_pool_head(const float *h, const float *g_fi
   const size_t need = (size_t)batch->total_tokens * sizeof(float);
   if (!ws || ws_bytes < need) return arb_fail(ARB_ECAPACITY, "arb_stage_norm_pool_head: workspace %zu < %zu bytes", ws_bytes, need);
   hipStream_t st = (hipStream_t)stream;
-  if (arb_status s = launch_final_norm_head(h, nullptr, 0, g_final, eps, batch->total_tokens, d, w_head, (bf16 *)hidden_out,
+  if (arb_status s = launch_final_norm_head(h, nullptr, 0, g_final, eps, batch->total_tokens, d, w_head, nullptr, (bf16 *)hidden_out,
                                             (float *)ws, st))
     return s;
-  return launch_pool_route((const float *)ws, batch->cu_step_lens, batch->batch, b_head, pool, tau, scores, escalate, st);
+  return launch_pool_route((const float *)ws, batch->cu_step_lens, batch->batch, b_head, pool, 0, tau, scores, escalate, st);
 }

@@ -107,9 +107,10 @@ arb_status launch_rope_append(bf16 *qkv, const float *parts, int n_parts, const 
                               bf16 *k_pool, bf16 *v_pool, int T, int n_q_heads, int n_kv_heads, int head_dim,
                               hipStream_t st);
 arb_status launch_final_norm_head(const float *h, const float *parts, int n_parts, const float *g, float eps, int T,
-                                  int d, const float *w_head, bf16 *hidden_out, float *tok_dot, hipStream_t st);
+                                  int d, const float *w_head, const float *w_head1, bf16 *hidden_out, float *tok_dot,
+                                  hipStream_t st);     // w_head1: class-1 row of a two-class head, else null
 arb_status launch_pool_route(const float *tok_dot, const int32_t *cu_step_lens, int batch, float b_head, int pool,
-                             float tau, float *scores, uint8_t *escalate, hipStream_t st);
+                             int probability, float tau, float *scores, uint8_t *escalate, hipStream_t st);
 arb_status launch_route(const float *scores, int n, float tau, int sense, uint8_t *escalate, hipStream_t st);
 arb_status launch_advantage_route(const float *s_t, const float *s_d, int n, float tau, const float *tau_device,
                                float *delta, uint8_t *escalate, float *realized, hipStream_t st);

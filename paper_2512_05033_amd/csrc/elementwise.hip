@@ -94,7 +94,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h_in, const f
                                                       const int32_t *__restrict__ token_ids,
                                                       const float *__restrict__ g, float eps, int d,
                                                       float *h_out, bf16 *__restrict__ x_out,
-                                                      const float *__restrict__ w_head, float *__restrict__ tok_dot) {
+                                                      const float *__restrict__ w_head,
+                                                      const float *__restrict__ w_head1, float *__restrict__ tok_dot) {
   __shared__ float red[4];
   const int row = blockIdx.x, tid = threadIdx.x;
   float v[ROW_VECS][8];
@@ -144,7 +145,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h_in, const f
 #pragma unroll
       for (int k = 0; k < 4; ++k) { y[k] = v[it][k] * r * g0[k]; y[4 + k] = v[it][4 + k] * r * g1[k]; }
       if (HEAD && w_head) {
-        const f32x4 w0 = *(const f32x4 *)(w_head + c), w1 = *(const f32x4 *)(w_head + c + 4);
+        f32x4 w0 = *(const f32x4 *)(w_head + c), w1 = *(const f32x4 *)(w_head + c + 4);
+        if (w_head1) {           // two-class head: only the difference of the class logits matters (class 1 minus class 0)
+          w0 = *(const f32x4 *)(w_head1 + c) - w0;
+          w1 = *(const f32x4 *)(w_head1 + c + 4) - w1;
+        }
 #pragma unroll
         for (int k = 0; k < 4; ++k) dot += y[k] * w0[k] + y[4 + k] * w1[k];
       }
@@ -174,7 +179,7 @@ arb_status launch_embed_rmsnorm(const bf16 *embed, const int32_t *token_ids, con
   if (arb_status s = check_row_width(d)) return s;
   hipLaunchKernelGGL((rmsnorm_kernel<true, false>), dim3(T), dim3(256), 0, st, (const float *)nullptr,
                      (const float *)nullptr, 0, (size_t)0, embed, token_ids, g, eps, d, h, x, (const float *)nullptr,
-                     (float *)nullptr);
+                     (const float *)nullptr, (float *)nullptr);
   ARB_CHECK_LAUNCH("embed_rmsnorm");
   return ARB_OK;
 }
@@ -185,19 +190,20 @@ arb_status launch_rmsnorm(float *h, const float *parts, int n_parts, const float
   if (arb_status s = check_row_width(d)) return s;
   hipLaunchKernelGGL((rmsnorm_kernel<false, false>), dim3(T), dim3(256), 0, st, (const float *)h, parts, n_parts,
                      (size_t)T * d, (const bf16 *)nullptr, (const int32_t *)nullptr, g, eps, d, h, x,
-                     (const float *)nullptr, (float *)nullptr);
+                     (const float *)nullptr, (const float *)nullptr, (float *)nullptr);
   ARB_CHECK_LAUNCH("rmsnorm");
   return ARB_OK;
 }
 
 arb_status launch_final_norm_head(const float *h, const float *parts, int n_parts, const float *g, float eps, int T,
-                                  int d, const float *w_head, bf16 *hidden_out, float *tok_dot, hipStream_t st) {
+                                  int d, const float *w_head, const float *w_head1, bf16 *hidden_out, float *tok_dot,
+                                  hipStream_t st) {
   if (T == 0) return ARB_OK;
   if (arb_status s = check_row_width(d)) return s;
   // the residual stream is not needed after the last norm, so the completed row is not written back
   hipLaunchKernelGGL((rmsnorm_kernel<false, true>), dim3(T), dim3(256), 0, st, h, parts, n_parts, (size_t)T * d,
                      (const bf16 *)nullptr, (const int32_t *)nullptr, g, eps, d, (float *)nullptr, hidden_out, w_head,
-                     tok_dot);
+                     w_head1, tok_dot);
   ARB_CHECK_LAUNCH("final_norm_head");
   return ARB_OK;
 }
@@ -281,10 +287,12 @@ arb_status launch_rope_append(bf16 *qkv, const float *parts, int n_parts, const 
 // One wave per sequence.  tok_dot[j] = w . y_j, so by linearity of the head
 // score_b = mean_j tok_dot[j] + c (mean pooling) or tok_dot[last] + c.
 // The sum runs in a fixed order, so repeated calls give identical bits.
+// With `probability` the pooled value is the difference of two class logits and the score is the
+// softmax probability of class 1, 1 / (1 + exp(-z)) (Sec. 4.2: the router's y_hat).
 // Decision (Alg. 1): accept iff score <= tau, i.e. escalate = !(score <= tau).
 __global__ __launch_bounds__(64) void pool_route_kernel(const float *__restrict__ tok_dot,
                                                         const int32_t *__restrict__ cu, float b_head, int pool,
-                                                        float tau, float *__restrict__ scores,
+                                                        int probability, float tau, float *__restrict__ scores,
                                                         uint8_t *__restrict__ escalate) {
   const int b = blockIdx.x, lo = cu[b], hi = cu[b + 1];
   float acc = 0.f;
@@ -294,7 +302,8 @@ __global__ __launch_bounds__(64) void pool_route_kernel(const float *__restrict_
     for (int j = lo + (int)threadIdx.x; j < hi; j += 64) acc += tok_dot[j];
     acc = wave_sum(acc) / (float)(hi - lo);
   }
-  const float score = acc + b_head;
+  float score = acc + b_head;
+  if (probability) score = 1.0f / (1.0f + expf(-score));
   if (threadIdx.x == 0) {
     scores[b] = score;
     if (escalate) escalate[b] = !(score <= tau);
@@ -302,10 +311,10 @@ __global__ __launch_bounds__(64) void pool_route_kernel(const float *__restrict_
 }
 
 arb_status launch_pool_route(const float *tok_dot, const int32_t *cu_step_lens, int batch, float b_head, int pool,
-                             float tau, float *scores, uint8_t *escalate, hipStream_t st) {
+                             int probability, float tau, float *scores, uint8_t *escalate, hipStream_t st) {
   if (batch == 0) return ARB_OK;
-  hipLaunchKernelGGL(pool_route_kernel, dim3(batch), dim3(64), 0, st, tok_dot, cu_step_lens, b_head, pool, tau, scores,
-                     escalate);
+  hipLaunchKernelGGL(pool_route_kernel, dim3(batch), dim3(64), 0, st, tok_dot, cu_step_lens, b_head, pool, probability,
+                     tau, scores, escalate);
   ARB_CHECK_LAUNCH("pool_route");
   return ARB_OK;
 }

@@ -44,9 +44,10 @@ def prompt_batch(w: W.Workload, batch: W.Batch, device="cuda") -> A.DeviceBatch:
 
 
 def setup(w: W.Workload, device="cuda", *, gain_jitter: float = 0.0, sigma: float = 0.02, b_head: float = 0.0,
-          pool: int = A.ARB_POOL_MEAN, batch: Optional[W.Batch] = None) -> Session:
+          pool: int = A.ARB_POOL_MEAN, batch: Optional[W.Batch] = None, two_class_head: bool = False) -> Session:
     batch = batch or W.make_batch(w)
-    weights = W.make_weights(w.model, w.seed, device, sigma=sigma, gain_jitter=gain_jitter, b_head=b_head)
+    weights = W.make_weights(w.model, w.seed, device, sigma=sigma, gain_jitter=gain_jitter, b_head=b_head,
+                             two_class_head=two_class_head)
     model = make_model(w.model, weights, pool)
     ks, vs = W.make_kv_pools(w, batch, device)
     kv = A.KVCache(ks, vs)

@@ -70,6 +70,8 @@ def test_model_create_validation(lib):
     assert _create(lib, _cfg(d_model=200), w)[0] == B.ARB_EUNSUPPORTED
     assert b"d_model" in lib.arb_last_error()
     assert _create(lib, _cfg(pool=7), w)[0] == B.ARB_EINVAL
+    assert _create(lib, _cfg(has_router_head=3), w)[0] == B.ARB_EINVAL
+    assert _create(lib, _cfg(has_router_head=B.ARB_HEAD_TWO_CLASS), w)[0] == B.ARB_OK
     wn, _k2 = _weights(head=False)
     assert _create(lib, _cfg(), wn)[0] == B.ARB_EINVAL
     assert _create(lib, _cfg(has_router_head=0), wn)[0] == B.ARB_OK

@@ -300,12 +300,15 @@ def _oracle_run(sess, pool_mode="mean"):
     return m, p
 
 
-def _end_to_end(A, w, *, gain_jitter=0.0, sigma=0.02, b_head=0.0, pool_mode="mean"):
+def _end_to_end(A, w, *, gain_jitter=0.0, sigma=0.02, b_head=0.0, pool_mode="mean", two_class_head=False, tau=None):
     h = H()
     pool = A.ARB_POOL_MEAN if pool_mode == "mean" else A.ARB_POOL_LAST
     batch = W.make_batch(w)
+    if tau is not None:
+        batch.tau = tau
     # oracle side first, from pristine pools
-    weights_cpu = W.make_weights(w.model, w.seed, "cpu", sigma=sigma, gain_jitter=gain_jitter, b_head=b_head)
+    weights_cpu = W.make_weights(w.model, w.seed, "cpu", sigma=sigma, gain_jitter=gain_jitter, b_head=b_head,
+                                 two_class_head=two_class_head)
     m, p = oracle_model(w.model), oracle_params(weights_cpu)
     kp, vp = oracle_pools(*W.make_kv_pools(w, batch, "cpu"))
     if w.kv_source == "prefill":
@@ -314,7 +317,8 @@ def _end_to_end(A, w, *, gain_jitter=0.0, sigma=0.02, b_head=0.0, pool_mode="mea
     kp_before = [a.copy() for a in kp]
     s_ref, e_ref, y_ref = O.score_steps(m, p, kp, vp, batch.token_ids, batch.prefix_lens, batch.cu_step_lens,
                                         batch.block_tables, batch.tau, pool_mode)
-    sess = h.setup(w, "cuda", gain_jitter=gain_jitter, sigma=sigma, b_head=b_head, pool=pool, batch=batch)
+    sess = h.setup(w, "cuda", gain_jitter=gain_jitter, sigma=sigma, b_head=b_head, pool=pool, batch=batch,
+                   two_class_head=two_class_head)
     scores, esc, hidden = A.arb_score_steps(sess.model, sess.kv, sess.dbatch, batch.tau, want_hidden=True, ws=sess.ws)
     torch.cuda.synchronize()
     return sess, (scores, esc, hidden), (s_ref, e_ref, y_ref), (kp, vp, kp_before)
@@ -363,6 +367,18 @@ def test_c1_with_large_weights_exercises_attention(A):
     end-to-end check really depends on the softmax."""
     sess, (scores, esc, hidden), (s_ref, e_ref, y_ref), _ = _end_to_end(A, W.C1, sigma=0.08, gain_jitter=0.1)
     assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+    _assert_scores(sess.batch, scores, esc, s_ref, e_ref)
+
+
+@pytest.mark.parametrize("pool_mode", ["mean", "last"])
+def test_c1_two_class_head_scores_are_probabilities(A, pool_mode):
+    """The two-way classification head of Section 4.2: scores are class-1 probabilities, tau is a probability."""
+    sess, (scores, esc, hidden), (s_ref, e_ref, y_ref), _ = _end_to_end(
+        A, W.C1, sigma=0.08, gain_jitter=0.1, b_head=-0.2, pool_mode=pool_mode, two_class_head=True, tau=0.45)
+    assert sess.model.cfg.has_router_head == A.ARB_HEAD_TWO_CLASS
+    assert rel_err(bf16_np(hidden), y_ref) < HIDDEN_TOL
+    s = scores.cpu().numpy()
+    assert np.all((s > 0) & (s < 1)) and np.ptp(s_ref) > 0.02       # real probabilities that differ between sequences
     _assert_scores(sess.batch, scores, esc, s_ref, e_ref)
 
 

@@ -433,6 +433,28 @@ def test_router_head_closed_forms():
     assert abs(mean[0] - last[0]) > 1e-6
 
 
+def test_two_class_head_is_the_logistic_of_the_folded_linear_head():
+    """Section 4.2 ('Training'): a two-way classification head.  Its class-1 probability depends only on
+    the logit difference, so it must equal the logistic function of the linear head with w = w_1 - w_0,
+    c = c_1 - c_0; thresholding the probability at tau_p is thresholding that linear score at
+    ln(tau_p / (1 - tau_p)) (0.5 <-> 0)."""
+    cu = np.array([0, 3, 4, 9], np.int32)
+    y = RNG.normal(0, 1, (9, 6)); w2 = RNG.normal(0, 1, (2, 6))
+    for mode in ("mean", "last"):
+        p = O.router_scores(y, cu, w2, 0.3, mode)
+        z = O.router_scores(y, cu, w2[1] - w2[0], 0.3, mode)
+        assert np.allclose(p, 1.0 / (1.0 + np.exp(-z)), atol=1e-14)
+        assert np.all((p > 0) & (p < 1))
+        for tau_p in (0.2, 0.5, 0.9):
+            assert np.array_equal(O.route(p, tau_p), O.route(z, np.log(tau_p / (1 - tau_p))))
+    # identical rows: the classes cannot be told apart; swapping the rows mirrors the probability
+    assert np.allclose(O.router_scores(y, cu, np.stack([w2[0], w2[0]]), 0.0), 0.5, atol=1e-15)
+    assert np.allclose(O.router_scores(y, cu, w2[::-1].copy(), -0.3), 1.0 - O.router_scores(y, cu, w2, 0.3), atol=1e-14)
+    # large logit differences saturate without overflow
+    big = O.router_scores(np.full((9, 6), 50.0), cu, np.stack([np.zeros(6), np.full(6, 20.0)]), 0.0)
+    assert np.all(big == 1.0) and np.all(np.isfinite(big))
+
+
 # --------------------------------------------------------------------------- decision
 
 def test_route_tie_nan_and_sense():

@@ -132,10 +132,11 @@ def _gain(seed: int, name: str, d: int, jitter: float, device) -> torch.Tensor:
 
 
 def make_weights(m: ModelShape, seed: int, device="cpu", sigma: float = 0.02,
-                 gain_jitter: float = 0.0, b_head: float = 0.0) -> Weights:
+                 gain_jitter: float = 0.0, b_head: float = 0.0, two_class_head: bool = False) -> Weights:
     """Matrices, embedding and head ~ N(0, sigma^2) rounded to bf16; RMSNorm gains
     are 1 (plus an optional bf16-representable jitter, used by tests so that a
-    dropped gain is visible)."""
+    dropped gain is visible).  two_class_head: the head is a [2, d] matrix (one row
+    per class) instead of a [d] vector; b_head then stands for the bias difference."""
     d, f, hq = m.d_model, m.d_ffn, m.n_q_heads * m.head_dim
     mk = lambda name, shape: normal_bf16(seed, name, shape, sigma, device)
     return Weights(
@@ -147,7 +148,7 @@ def make_weights(m: ModelShape, seed: int, device="cpu", sigma: float = 0.02,
         g_attn=[_gain(seed, f"L{l}.g_attn", d, gain_jitter, device) for l in range(m.n_layers)],
         g_mlp=[_gain(seed, f"L{l}.g_mlp", d, gain_jitter, device) for l in range(m.n_layers)],
         g_final=_gain(seed, "g_final", d, gain_jitter, device),
-        w_head=normal_bf16(seed, "w_head", (d,), sigma, device).float(),
+        w_head=normal_bf16(seed, "w_head", (2, d) if two_class_head else (d,), sigma, device).float(),
         b_head=b_head,
     )
 
