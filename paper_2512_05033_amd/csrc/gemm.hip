@@ -183,10 +183,20 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
 // steps in flight instead of one.  LDS rows are 64 bytes here; chunks are swizzled by row/4.
 // MI = 32-row MFMA tiles per wave along M: 2 gives the 128x128 tile, 1 a 64x128 tile for launches
 // that would otherwise leave more than half of the CUs without a workgroup.
-constexpr int RK = 32, RING_STAGES = 8;
+#ifndef ARB_RING_K
+#define ARB_RING_K 64
+#endif
+constexpr int RK = ARB_RING_K;                      // K per stage: 64 makes every row piece a whole 128-byte line
+constexpr int ring_stages(int mi) { return RK == 32 ? 8 : (mi == 1 ? 6 : 4); }   // 128 KB (144 KB: 64-row tile, K 64)
 
 __device__ __forceinline__ int lds_off32(int row, int chunk) {   // element offset of a 16-byte chunk, 64-byte rows
   return row * 32 + ((chunk ^ ((row >> 2) & 3)) << 3);
+}
+
+__device__ __forceinline__ int lds_off_ring(int row, int chunk) {   // element offset of a 16-byte chunk in a stage row
+  // 16 lanes read 16 consecutive rows of one chunk: 64-byte rows put 4 rows into 256 bytes (swizzle by row/4),
+  // 128-byte rows 2 (swizzle by row/2)
+  return RK == 32 ? row * 32 + ((chunk ^ ((row >> 2) & 3)) << 3) : row * 64 + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
 // s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, lgkmcnt in 11:8, expcnt 6:4 left at "no wait")
@@ -197,11 +207,18 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
                                                    void *__restrict__ Cv, int M, int N, int K, int tiles_m,
                                                    int tiles_n, int tile_n0) {
   constexpr int RBM = 64 * MI;                              // rows of the tile
+  constexpr int RING_STAGES = ring_stages(MI);
   constexpr int RING_STAGE_ELEMS = (RBM + BN) * RK;         // A rows then B rows
-  constexpr int LOADS = MI + 2;                             // wave-wide loads per wave and step
+  constexpr int CPR = RK / 8, RPL = 64 / CPR;               // 16-byte chunks per stage row; rows per wave-wide load
+  constexpr int A_LOADS = RBM / (4 * RPL), B_LOADS = BN / (4 * RPL);   // wave-wide loads per wave and step
+  constexpr int LOADS = A_LOADS + B_LOADS;
+  constexpr int NS = RK / 16;                               // MFMA sub-steps per stage
+  constexpr int UNUSED = 8;
   // one array per stage (the compiler orders LDS reads against in-flight loads by object)
   __shared__ __attribute__((aligned(16))) bf16 St0[RING_STAGE_ELEMS], St1[RING_STAGE_ELEMS], St2[RING_STAGE_ELEMS],
-      St3[RING_STAGE_ELEMS], St4[RING_STAGE_ELEMS], St5[RING_STAGE_ELEMS], St6[RING_STAGE_ELEMS], St7[RING_STAGE_ELEMS];
+      St3[RING_STAGE_ELEMS], St4[RING_STAGES > 4 ? RING_STAGE_ELEMS : UNUSED], St5[RING_STAGES > 5 ? RING_STAGE_ELEMS : UNUSED],
+      St6[RING_STAGES > 6 ? RING_STAGE_ELEMS : UNUSED], St7[RING_STAGES > 7 ? RING_STAGE_ELEMS : UNUSED];
+  static_assert(RING_STAGES >= 4 && RING_STAGES <= 8, "stage arrays");
 #define ARB_ST(s) ((s) == 0 ? St0 : (s) == 1 ? St1 : (s) == 2 ? St2 : (s) == 3 ? St3 : (s) == 4 ? St4 : (s) == 5 ? St5 : (s) == 6 ? St6 : St7)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -211,22 +228,26 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   tile_n += tile_n0;                 // this launch covers n-tiles [tile_n0, tile_n0 + tiles_n)
   const int m0 = tile_m * RBM;
 
-  // This thread's 16-byte chunks per step: tile rows tid/4 + 64 i of A (i < MI) and of B (i < 2), the
-  // same chunk for all (the swizzle term (row/4)%4 does not depend on i).
-  const int row0 = tid >> 2, chunk = (tid & 3) ^ ((row0 >> 2) & 3);
-  const bf16 *a_src[MI];
+  // This thread's 16-byte chunks per step: tile rows row0 + 4 RPL i of A (i < A_LOADS) and of B (i < B_LOADS),
+  // the same chunk for all (the swizzle term of a row does not change when 4 RPL is added to it).
+  const int row0 = tid / CPR;
+  const int chunk = (tid % CPR) ^ (RK == 32 ? ((row0 >> 2) & 3) : ((row0 >> 1) & 7));
+  const bf16 *a_src[A_LOADS];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    int am = m0 + row0 + 64 * i;
+  for (int i = 0; i < A_LOADS; ++i) {
+    int am = m0 + row0 + 4 * RPL * i;
     am = am < M ? am : M - 1;                       // tail rows re-read the last row; never stored
     a_src[i] = A + (size_t)am * K + chunk * 8;
   }
-  // B rows of chunk i are b_row0 + i * (rows per i).  For SwiGLU the tile-local row r maps to wave column
-  // r/64, MFMA tile (r%64)/32 (0 = gate, 1 = up) and feature offset r%32, i.e. feature
-  // tile_n*64 + (r/64)*32 + r%32 of the gate or up half; N = F there.
-  const int b_row0 = EPI == ARB_EPI_SWIGLU_BF16 ? tile_n * 64 + (row0 & 31) + ((row0 >> 5) & 1) * N : tile_n * BN + row0;
-  const size_t b_step = (size_t)(EPI == ARB_EPI_SWIGLU_BF16 ? 32 : 64) * K;
-  const bf16 *b_src = B + (size_t)b_row0 * K + chunk * 8;
+  // B rows.  For SwiGLU the tile-local row r maps to wave column r/64, MFMA tile (r%64)/32 (0 = gate, 1 = up) and
+  // feature offset r%32, i.e. feature tile_n*64 + (r/64)*32 + r%32 of the gate or up half; N = F there.
+  const bf16 *b_src[B_LOADS];
+#pragma unroll
+  for (int i = 0; i < B_LOADS; ++i) {
+    const int r = row0 + 4 * RPL * i;
+    const int brow = EPI == ARB_EPI_SWIGLU_BF16 ? tile_n * 64 + (r >> 6) * 32 + (r & 31) + ((r >> 5) & 1) * N : tile_n * BN + r;
+    b_src[i] = B + (size_t)brow * K + chunk * 8;
+  }
 
   f32x16 acc[MI][2];
 #pragma unroll
@@ -241,26 +262,30 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   const int kt_begin = (int)((long long)nk_all * blockIdx.y / gridDim.y);
   const int nk = (int)((long long)nk_all * (blockIdx.y + 1) / gridDim.y) - kt_begin, last = nk - 1;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) a_src[i] += (size_t)kt_begin * RK;
-  b_src += (size_t)kt_begin * RK;
+  for (int i = 0; i < A_LOADS; ++i) a_src[i] += (size_t)kt_begin * RK;
+#pragma unroll
+  for (int i = 0; i < B_LOADS; ++i) b_src[i] += (size_t)kt_begin * RK;
 
   const int frag_row = lane & 31, frag_half = lane >> 5;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto dma_a = [&](int s, int kt) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < A_LOADS; ++i)
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + (i * 4 + wave_u) * 512), 16, 0, 0);
   };
   auto dma_b = [&](int s, int kt) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src + i * b_step + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + RBM * RK + (i * 4 + wave_u) * 512), 16, 0, 0);
+    for (int i = 0; i < B_LOADS; ++i)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src[i] + (size_t)kt * RK), LDS_PTR(ARB_ST(s) + RBM * RK + (i * 4 + wave_u) * 512), 16, 0, 0);
   };
   // The swizzle term of a fragment row depends on frag_row only, so each operand needs one LDS offset
   // per sub-step; MFMA tile and stage are constant displacements from it.
-  const int a_off[2] = {lds_off32(wm * 32 * MI + frag_row, frag_half), lds_off32(wm * 32 * MI + frag_row, 2 + frag_half)};
-  const int b_off[2] = {RBM * RK + lds_off32(wn * 64 + frag_row, frag_half),
-                        RBM * RK + lds_off32(wn * 64 + frag_row, 2 + frag_half)};
+  int a_off[NS], b_off[NS];
+#pragma unroll
+  for (int kk = 0; kk < NS; ++kk) {
+    a_off[kk] = lds_off_ring(wm * 32 * MI + frag_row, 2 * kk + frag_half);
+    b_off[kk] = RBM * RK + lds_off_ring(wn * 64 + frag_row, 2 * kk + frag_half);
+  }
   bf16x8 fa[2][MI], fb[2][2];
   auto frags = [&](int slot, int s, int kk) {
 #pragma unroll
@@ -275,20 +300,23 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
       for (int j = 0; j < 2; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
   };
-  // Step out of stage s (two sub-steps of 2 MI MFMAs); on entry fragment slot 0 holds its first sub-step.
+  // Step out of stage s (NS sub-steps of 2 MI MFMAs); on entry fragment slot 0 holds its first sub-step.
   // `refill` is the step loaded into the stage before s, which every wave left at the previous barrier
   // (clamped to the last step past the end; those copies are never read).  Before the barrier this
   // wave's reads of stage s have returned and its loads of the next step have landed: they are the
-  // oldest of its loads in flight, the LOADS * (RING_STAGES - 3) + MI issued since may stay in flight.  (A full
+  // oldest of its loads in flight, the LOADS * (RING_STAGES - 3) + A_LOADS issued since may stay in flight.  (A full
   // workgroup fence would wait for all of them.)
   auto step = [&](int s, int refill) {
     const int prev = (s + RING_STAGES - 1) % RING_STAGES, next = (s + 1) % RING_STAGES;
-    frags(1, s, 1);
-    dma_a(prev, refill);
-    __builtin_amdgcn_sched_barrier(0);
-    mfmas(0);
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LOADS * (RING_STAGES - 3) + MI));
+#pragma unroll
+    for (int kk = 0; kk + 1 < NS; ++kk) {
+      frags((kk + 1) & 1, s, kk + 1);
+      if (kk == 0) dma_a(prev, refill);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(kk & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(LOADS * (RING_STAGES - 3) + A_LOADS));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     frags(0, next, 0);
@@ -300,10 +328,13 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   // The same without a refill, for the steps after the last whole turn of the ring: nothing is loaded
   // any more, so the wait is for everything still in flight.
   auto drain_step = [&](int s) {
-    frags(1, s, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfmas(0);
-    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk + 1 < NS; ++kk) {
+      frags((kk + 1) & 1, s, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(kk & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -564,9 +595,11 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
 int gemm_residual_splits(int M, int N, int K) {
   // as many workgroups as are resident at once (two per CU on 256 CUs) without starting a second
   // round, each keeping at least 4 K-steps; the partials cost 8 bytes of traffic per element and
-  // split, so no more splits than that (measured on the 1.5B shape: 5 beats 4 and 6)
+  // split, so no more splits than that (measured on the 1.5B shape: 5 beats 4 and 6 for K = 8960).
+  // With a short K (at most 32 steps) the launch is kept to one workgroup per CU instead, which the
+  // deep-ring kernel serves better and which halves the partial traffic (measured: 2 beats 5 for K = 1536).
   const int tiles = ceil_div(M, BM) * (N / BN), nk = K / BK;
-  int s = 512 / tiles;
+  int s = (nk <= 32 ? 256 : 512) / tiles;
   if (s > nk / 4) s = nk / 4;
   if (s > 8) s = 8;
   return s < 1 ? 1 : s;
