@@ -40,7 +40,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  constexpr int TILE_GROUP = 4;
+  tile_of<TILE_GROUP>(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
   tile_n += tile_n0;                 // this launch covers n-tiles [tile_n0, tile_n0 + tiles_n)
   const int m0 = tile_m * BM;
 
@@ -224,7 +225,8 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  constexpr int TILE_GROUP = MI == 1 ? 8 : 4;      // 512 rows
+  tile_of<TILE_GROUP>(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
   tile_n += tile_n0;                 // this launch covers n-tiles [tile_n0, tile_n0 + tiles_n)
   const int m0 = tile_m * RBM;
 
@@ -433,7 +435,8 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  constexpr int TILE_GROUP = 4;
+  tile_of<TILE_GROUP>(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * LM;
 
   // This thread's four 16-byte chunks per operand and step: tile rows tid/4 + 64 i, and the same

@@ -75,7 +75,8 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict_
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  constexpr int TILE_GROUP = 4;
+  tile_of<TILE_GROUP>(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM;
   const int frag_row = lane & 31, frag_half = lane >> 5;
 
