@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const bf16 *__restrict__ A
 #define ARB_RING_K 64
 #endif
 constexpr int RK = ARB_RING_K;                      // K per stage: 64 makes every row piece a whole 128-byte line
-constexpr int ring_stages(int mi) { return RK == 32 ? 8 : (mi == 1 ? 6 : 4); }   // 128 KB (144 KB: 64-row tile, K 64)
+constexpr int ring_stages(int mi) { return RK == 32 ? 8 : (mi == 1 ? 6 : mi == 2 ? 4 : 3); }   // 144, 128, 144 KB for K 64
 
 __device__ __forceinline__ int lds_off32(int row, int chunk) {   // element offset of a 16-byte chunk, 64-byte rows
   return row * 32 + ((chunk ^ ((row >> 2) & 3)) << 3);
@@ -217,15 +217,15 @@ __global__ __launch_bounds__(256, 1) void gemm_ring_kernel(const bf16 *__restric
   constexpr int UNUSED = 8;
   // one array per stage (the compiler orders LDS reads against in-flight loads by object)
   __shared__ __attribute__((aligned(16))) bf16 St0[RING_STAGE_ELEMS], St1[RING_STAGE_ELEMS], St2[RING_STAGE_ELEMS],
-      St3[RING_STAGE_ELEMS], St4[RING_STAGES > 4 ? RING_STAGE_ELEMS : UNUSED], St5[RING_STAGES > 5 ? RING_STAGE_ELEMS : UNUSED],
+      St3[RING_STAGES > 3 ? RING_STAGE_ELEMS : UNUSED], St4[RING_STAGES > 4 ? RING_STAGE_ELEMS : UNUSED], St5[RING_STAGES > 5 ? RING_STAGE_ELEMS : UNUSED],
       St6[RING_STAGES > 6 ? RING_STAGE_ELEMS : UNUSED], St7[RING_STAGES > 7 ? RING_STAGE_ELEMS : UNUSED];
-  static_assert(RING_STAGES >= 4 && RING_STAGES <= 8, "stage arrays");
+  static_assert(RING_STAGES >= 3 && RING_STAGES <= 8, "stage arrays");
 #define ARB_ST(s) ((s) == 0 ? St0 : (s) == 1 ? St1 : (s) == 2 ? St2 : (s) == 3 ? St3 : (s) == 4 ? St4 : (s) == 5 ? St5 : (s) == 6 ? St6 : St7)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  constexpr int TILE_GROUP = MI == 1 ? 8 : 4;      // 512 rows
+  constexpr int TILE_GROUP = 512 / RBM;            // 512 rows
   tile_of<TILE_GROUP>(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
   tile_n += tile_n0;                 // this launch covers n-tiles [tile_n0, tile_n0 + tiles_n)
   const int m0 = tile_m * RBM;
@@ -658,11 +658,18 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   const dim3 block(256);
   const bool ring = tiles_m * tiles_n * splits <= 256;      // at most one workgroup per CU: latency-bound
   const bool half = tiles_m * tiles_n * splits <= 128;      // not even half of the CUs: 64-row tiles
+  // More than one round of 128-row tiles that is one well-filled round of 256-row tiles (the split-K down
+  // projection): the taller tile reads 0.75 KB of LDS per MFMA instead of 1 KB, needs a third less ingest
+  // per flop and runs on the deep-ring kernel.
+  const int tm256 = ceil_div(M, 256);
+  const bool tall = !ring && tm256 * tiles_n * splits <= 256 && tm256 * tiles_n * splits >= 192;
   const int tm64 = ceil_div(M, 64);
-  const dim3 grid(tiles_m * tiles_n, splits), grid64(tm64 * tiles_n, splits);
+  const dim3 grid(tiles_m * tiles_n, splits), grid64(tm64 * tiles_n, splits), grid256(tm256 * tiles_n, splits);
 #define ARB_SMALL(E)                                                                                                  \
   do {                                                                                                                \
-    if (half)                                                                                                         \
+    if (tall)                                                                                                         \
+      hipLaunchKernelGGL((gemm_ring_kernel<E, 4>), grid256, block, 0, st, A, B, C, M, N, K, tm256, tiles_n, tile_n0); \
+    else if (half)                                                                                                    \
       hipLaunchKernelGGL((gemm_ring_kernel<E, 1>), grid64, block, 0, st, A, B, C, M, N, K, tm64, tiles_n, tile_n0);   \
     else if (ring)                                                                                                    \
       hipLaunchKernelGGL((gemm_ring_kernel<E, 2>), grid, block, 0, st, A, B, C, M, N, K, tiles_m, tiles_n, tile_n0);  \

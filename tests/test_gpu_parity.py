@@ -61,7 +61,8 @@ def test_slot_mapping_bit_exact(A, name):
 @pytest.mark.parametrize("M,N,K", [(1, 128, 64), (200, 256, 192), (1024, 2048, 1536), (333, 1536, 8960),
                                    (3300, 4096, 256),    # 256x256-tile kernel alone (208 tiles)
                                    (4000, 8960, 128),    # 560 large tiles: 32 n-columns in 256x256 tiles, the other 3 in 128x128 tiles
-                                   (16, 1536, 8960), (33, 2048, 1536), (64, 128, 576), (5, 256, 64)])   # decode-sized M
+                                   (16, 1536, 8960), (33, 2048, 1536), (64, 128, 576), (5, 256, 64),   # decode-sized M
+                                   (2048, 3072, 576), (1900, 3072, 448)])   # one round of 256x128 tiles (3-stage ring: whole turns, remainder; ragged M)
 def test_gemm_store_and_residual(A, M, N, K):
     a, b = rand_bf16((M, K), 1.0, 11), rand_bf16((N, K), 0.02, 12)
     ref = bf16_np(a) @ bf16_np(b).T
@@ -76,7 +77,8 @@ def test_gemm_store_and_residual(A, M, N, K):
 @pytest.mark.parametrize("M,F,K", [(130, 64, 128), (1024, 8960, 1536), (1000, 8960, 192),
                                    (3300, 2048, 128),    # 256x256-tile kernel alone (208 tiles)
                                    (2000, 8960, 128),    # 560 large tiles: 64 n-columns in large tiles, the other 6 in small ones
-                                   (16, 8960, 1536), (40, 192, 320), (1, 64, 64)])   # decode-sized M
+                                   (16, 8960, 1536), (40, 192, 320), (1, 64, 64),   # decode-sized M
+                                   (2048, 1792, 320)])   # one round of 256x128 tiles
 def test_gemm_swiglu(A, M, F, K):
     a, b = rand_bf16((M, K), 1.0, 13), rand_bf16((2 * F, K), 0.05, 14)
     af, bf = bf16_np(a), bf16_np(b)
