@@ -21,8 +21,8 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # Counter runs of the dominant kernel on workload C2 (profiles/score_steps_C2_hbm_traffic.txt): scaled
 # FETCH_SIZE + WRITE_SIZE bytes per launch, and the SHA-256 of the csrc/gemm.hip they were taken with.
-COUNTED_GATE_UP_BYTES = 75825301 + 20802571
-COUNTED_GEMM_SHA256 = "b16446511351f99599cb02a1e85593a2f50fba3e6a169136d4de714933772cbb"
+COUNTED_GATE_UP_BYTES = 75847884 + 20747485
+COUNTED_GEMM_SHA256 = "8bfbb7995424e08a98f4f4ece61248e979d68540952edd8d01d4c94c2d92ccd1"
 
 
 def cpu_baseline(w, sess, layers: int):
