@@ -115,11 +115,32 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *h_in, const f
         const float *src = h_in + (size_t)row * d + c;
         f32x4 a = *(const f32x4 *)src, b = *(const f32x4 *)(src + 4);
         if (n_parts > 0) {
-          for (int sp = 0; sp < n_parts; ++sp) {
-            const float *ps = parts + sp * part_stride + (size_t)row * d + c;
-            a += *(const f32x4 *)ps;
-            b += *(const f32x4 *)(ps + 4);
+          // For the usual split counts the loads of all partial products go out together (a loop over a
+          // run-time count waits for each before it asks for the next); the sums keep the fixed order.
+          const float *p0 = parts + (size_t)row * d + c;
+#define ARB_ADD_PARTS(NP)                                                      \
+  {                                                                            \
+    f32x4 pa[NP], pb[NP];                                                      \
+    _Pragma("unroll") for (int sp = 0; sp < NP; ++sp) {                        \
+      pa[sp] = *(const f32x4 *)(p0 + sp * part_stride);                        \
+      pb[sp] = *(const f32x4 *)(p0 + sp * part_stride + 4);                    \
+    }                                                                          \
+    _Pragma("unroll") for (int sp = 0; sp < NP; ++sp) { a += pa[sp]; b += pb[sp]; } \
+  }
+          switch (n_parts) {
+            case 1: ARB_ADD_PARTS(1) break;
+            case 2: ARB_ADD_PARTS(2) break;
+            case 3: ARB_ADD_PARTS(3) break;
+            case 4: ARB_ADD_PARTS(4) break;
+            case 5: ARB_ADD_PARTS(5) break;
+            case 8: ARB_ADD_PARTS(8) break;
+            default:
+              for (int sp = 0; sp < n_parts; ++sp) {
+                a += *(const f32x4 *)(p0 + sp * part_stride);
+                b += *(const f32x4 *)(p0 + sp * part_stride + 4);
+              }
           }
+#undef ARB_ADD_PARTS
           if (h_out) {                          // the last norm of a pass has no later reader of h
             float *dst = h_out + (size_t)row * d + c;
             *(f32x4 *)dst = a;
