@@ -62,7 +62,11 @@ def test_slot_mapping_bit_exact(A, name):
                                    (3300, 4096, 256),    # 256x256-tile kernel alone (208 tiles)
                                    (4000, 8960, 128),    # 560 large tiles: 32 n-columns in 256x256 tiles, the other 3 in 128x128 tiles
                                    (16, 1536, 8960), (33, 2048, 1536), (64, 128, 576), (5, 256, 64),   # decode-sized M
-                                   (2048, 3072, 576), (1900, 3072, 448)])   # one round of 256x128 tiles (3-stage ring: whole turns, remainder; ragged M)
+                                   (2048, 3072, 576), (1900, 3072, 448),   # one round of 256x128 tiles (3-stage ring: whole turns, remainder; ragged M)
+                                   # the launch rules at their boundaries: 256 tiles of 128 rows (ring) and 272 (two
+                                   # workgroups per CU), 128 tiles (64-row ring tiles), 256 tiles of 256 rows (tall),
+                                   # 204 large tiles (one short of the large-tile kernel)
+                                   (2048, 2048, 128), (2048, 2176, 64), (1024, 2048, 192), (4096, 2048, 128), (3072, 4352, 64)])
 def test_gemm_store_and_residual(A, M, N, K):
     a, b = rand_bf16((M, K), 1.0, 11), rand_bf16((N, K), 0.02, 12)
     ref = bf16_np(a) @ bf16_np(b).T
