@@ -554,20 +554,31 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
 #undef ARB_STAGE
 
   if (EPI == ARB_EPI_SWIGLU_BF16) {
+    // A lane holds single elements of 128 rows: stored from registers they would leave in 2-byte
+    // pieces (128 stores per lane through the address unit).  The wave's 128 x 64 block goes through
+    // the LDS instead (the stages are free now, 16 KB per wave) and leaves in 16-byte pieces of whole
+    // 128-byte rows.  The 16-byte chunks of a row are swizzled by bit 2 of the row so that the two
+    // lane halves, four rows apart, write different banks.
     bf16 *C = (bf16 *)Cv;
+    __syncthreads();                      // every wave is done reading the last stage
+    bf16 *stage = wave_u == 0 ? As0 : wave_u == 1 ? As1 : wave_u == 2 ? As2 : As3;
 #pragma unroll
-    for (int jp = 0; jp < 2; ++jp) {
-      const int col = tile_n * 128 + wn * 64 + jp * 32 + frag_row;
+    for (int jp = 0; jp < 2; ++jp)
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-          if (m < M) {
-            const float gte = acc[i][2 * jp][r], up = acc[i][2 * jp + 1][r];
-            C[(size_t)m * N + col] = (bf16)(gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up);
-          }
+          const int row = i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3), f = jp * 32 + frag_row;
+          const float gte = acc[i][2 * jp][r], up = acc[i][2 * jp + 1][r];
+          stage[row * 64 + ((((f >> 3) ^ (((row >> 2) & 1) << 2))) << 3) + (f & 7)] =
+              (bf16)(gte * __builtin_amdgcn_rcpf(1.0f + __expf(-gte)) * up);
         }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int row = it * 8 + (lane >> 3), chunk = lane & 7;
+      const bf16x8 v = *(const bf16x8 *)&stage[row * 64 + ((chunk ^ (((row >> 2) & 1) << 2)) << 3)];
+      const int m = m0 + wm * 128 + row;
+      if (m < M) *(bf16x8 *)(C + (size_t)m * N + tile_n * 128 + wn * 64 + chunk * 8) = v;
     }
   } else {
 #pragma unroll
