@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0
 # Counter runs of the dominant kernel on workload C2 (profiles/score_steps_C2_hbm_traffic.txt): scaled
 # FETCH_SIZE + WRITE_SIZE bytes per launch, and the SHA-256 of the csrc/gemm.hip they were taken with.
 COUNTED_GATE_UP_BYTES = 75765665 + 16777216
-COUNTED_GEMM_SHA256 = "bf58c5ce0163b386e149f7da9bbe186d70900c60a04b9d2554d0939b24bac6f4"
+COUNTED_GEMM_SHA256 = "4087d989fdc51d83d158cef81f68ae558f36e86957e621ae1f8927def421f662"
 
 
 def cpu_baseline(w, sess, layers: int):
