@@ -363,7 +363,7 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const bf16 *__rest
 }  // namespace
 
 static const int kTargetWorkgroups = 512;    // two resident workgroups per CU on 256 CUs
-static const int kMinChunk = 256, kMaxChunk = 2048, kMaxSplits = 64;
+static const int kMinChunk = 256, kMaxChunk = 4096, kMaxChunkDecode = 8192, kMaxSplits = 64;
 
 int attention_splits_cap(int max_ctx) {
   if (max_ctx <= 0) return 1;
@@ -382,9 +382,13 @@ AttnPlan plan_attention(int batch, const int32_t *prefix_host, const int32_t *cu
   }
   // Keys per split: about kTargetWorkgroups workgroups (one resident round) when contexts are short,
   // so that few partial states have to be merged; never more than kMaxChunk keys, so that long
-  // ragged contexts become many rounds of similar-sized workgroups instead of one unbalanced round.
+  // ragged contexts become several rounds of similar-sized workgroups instead of one unbalanced round
+  // (measured on the ragged workloads: 4096 beats 2048 by 2-3 %, 8192 loses).  A batch whose steps all
+  // fit one wave (32 query rows: drafting token by token) only streams the cache: there the longer
+  // chunk of kMaxChunkDecode wins (fewer prologues and partial states: 5.3 -> 5.7 TB/s).
+  const int cap = max_step * G <= 32 ? kMaxChunkDecode : kMaxChunk;
   long long chunk = (keys_streamed / kTargetWorkgroups + KT - 1) / KT * KT;
-  if (chunk > kMaxChunk) chunk = kMaxChunk;
+  if (chunk > cap) chunk = cap;
   if (chunk < kMinChunk) chunk = kMinChunk;
   while (max_ctx > chunk * kMaxSplits) chunk += KT;
   AttnPlan pl;
