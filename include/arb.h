@@ -101,6 +101,11 @@ typedef struct {
    * [rows, in/128], and wqkv/wo/wgu/wd point at the packed integers uint32 [rows, in/8] of
    * arb_w4_quantize instead of bf16 values (same row order).  Embedding, gains and head stay as above. */
   const void *const *wqkv_scale, *const *wo_scale, *const *wgu_scale, *const *wd_scale;
+  /* Optional second copy of the gate/up weights in the K-blocked layout of arb_pack_k_blocked (bf16 weights
+   * only): NULL, or a HOST array of n_layers DEVICE pointers.  The gate/up projection's large-tile kernel
+   * then reads whole cache lines (about 6 % faster on the 1.5B shape); results are bit-identical.  wgu is
+   * still required (the rest of the projection reads it).  Costs 4 F d bytes per layer. */
+  const void *const *wgu_blocked;
 } arb_weights;
 
 /* Paged KV cache.  k_pool / v_pool are HOST arrays of n_layers DEVICE pointers;
@@ -217,9 +222,16 @@ typedef enum {
 } arb_gemm_epilogue;
 
 /* Projection GEMM: A bf16 [M, K] row-major, B bf16 [N, K] row-major (weights),
- * fp32 accumulation.  K % 64 == 0 and N % 128 == 0 (N % 64 == 0 for SWIGLU). */
-arb_status arb_stage_gemm(const void *A, const void *B, void *C, int32_t M, int32_t N, int32_t K, int32_t epilogue,
-                          void *stream);
+ * fp32 accumulation.  K % 64 == 0 and N % 128 == 0 (N % 64 == 0 for SWIGLU).  B_blocked: NULL, or the
+ * arb_pack_k_blocked copy of B, which the large-tile kernel then reads in B's place. */
+arb_status arb_stage_gemm(const void *A, const void *B, const void *B_blocked, void *C, int32_t M, int32_t N,
+                          int32_t K, int32_t epilogue, void *stream);
+
+/* K-blocked copy of a bf16 weight matrix W [rows, K] (K % 32 == 0), both on the device:
+ * packed[(kb * rows + r) * 32 + j] = W[r][kb * 32 + j], i.e. [K/32][rows][32], so that the same 32 inputs
+ * of consecutive rows are consecutive in memory.  For callers that cannot spare the copy the model works without it
+ * (arb_weights.wgu_blocked). */
+arb_status arb_pack_k_blocked(const void *W, int64_t rows, int32_t K, void *packed, void *stream);
 
 /* 4-bit weight format of the quantized draft (Section 5.1; the paper takes its integers from GPTQ /
  * llama.cpp, the forward only needs integers and group scales): per row and group of 128 consecutive

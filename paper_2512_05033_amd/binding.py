@@ -26,7 +26,7 @@ ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16, ARB_EPI_STORE_F32
 _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4: "ARB_EHIP", 5: "ARB_EUNSUPPORTED"}
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
-           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_w4_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
+           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_pack_k_blocked", "arb_w4_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
            "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
@@ -48,7 +48,8 @@ class _Weights(C.Structure):
                 ("wgu", C.POINTER(C.c_void_p)), ("wd", C.POINTER(C.c_void_p)), ("g_attn", C.POINTER(C.c_void_p)),
                 ("g_mlp", C.POINTER(C.c_void_p)), ("g_final", C.c_void_p), ("w_head", C.c_void_p),
                 ("b_head", C.c_float), ("wqkv_scale", C.POINTER(C.c_void_p)), ("wo_scale", C.POINTER(C.c_void_p)),
-                ("wgu_scale", C.POINTER(C.c_void_p)), ("wd_scale", C.POINTER(C.c_void_p))]
+                ("wgu_scale", C.POINTER(C.c_void_p)), ("wd_scale", C.POINTER(C.c_void_p)),
+                ("wgu_blocked", C.POINTER(C.c_void_p))]
 
 
 class _KV(C.Structure):
@@ -91,9 +92,10 @@ def load_library(path: Optional[str] = None):
     lib.arb_first_stop.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_void_p]
     lib.arb_slot_mapping.argtypes = [C.POINTER(_Batch), C.c_int32, C.c_void_p, C.c_void_p]
-    lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                                   C.c_void_p]
+    lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                   C.c_int32, C.c_void_p]
     lib.arb_w4_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.arb_pack_k_blocked.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_gemm_w4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                       C.c_int32, C.c_void_p]
     lib.arb_stage_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(_Batch),
@@ -149,7 +151,10 @@ class Model:
     """An arb_model plus the tensors it points at (kept alive here)."""
 
     def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, weights,
-                 rms_eps=1e-6, rope_base=10000.0, kv_block=16, pool=ARB_POOL_MEAN, has_router_head=True):
+                 rms_eps=1e-6, rope_base=10000.0, kv_block=16, pool=ARB_POOL_MEAN, has_router_head=True,
+                 block_gate_up=True):
+        """block_gate_up: also hand the library K-blocked copies of the gate/up weights (arb_pack_k_blocked; made
+        here on the weights' device, 4 F d bytes per layer); bf16 weights only."""
         lib = load_library()
         w = weights
         bf, f32 = torch.bfloat16, torch.float32
@@ -171,8 +176,14 @@ class Model:
         if scales is not None:
             self._keep += [_dev(t, bf) for l in scales for t in l]
             self._scale_arrays = [_ptr_array(l) for l in scales]
-        cw = _Weights(w.embed.data_ptr(), *self._arrays, w.g_final.data_ptr(),
-                      w.w_head.data_ptr() if has_router_head else None, float(w.b_head), *self._scale_arrays)
+        blocked = None
+        if block_gate_up and scales is None and w.wgu[0].is_cuda and d_model % 32 == 0:
+            self._keep += (packed := [arb_pack_k_blocked(t) for t in w.wgu])
+            torch.cuda.synchronize(w.embed.device)  # packed on torch's stream; callers may use any other
+            blocked = _ptr_array(packed)
+            self._arrays.append(blocked)           # keeps the pointer table alive
+        cw = _Weights(w.embed.data_ptr(), *self._arrays[:6], w.g_final.data_ptr(),
+                      w.w_head.data_ptr() if has_router_head else None, float(w.b_head), *self._scale_arrays, blocked)
         self.handle = C.c_void_p()
         _check(lib.arb_model_create(C.byref(self.cfg), C.byref(cw), C.byref(self.handle)))
         self.weights = w
@@ -329,9 +340,11 @@ def arb_slot_mapping(batch: DeviceBatch, kv_block: int = 16, stream=None) -> tor
 
 
 def arb_stage_gemm(a: torch.Tensor, b: torch.Tensor, epilogue: int = ARB_EPI_STORE_BF16,
-                   out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """a bf16 [M, K], b bf16 [N, K] (or [2F, K] for SwiGLU) -> [M, N] (or [M, F])."""
+                   out: Optional[torch.Tensor] = None, stream=None, b_blocked: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """a bf16 [M, K], b bf16 [N, K] (or [2F, K] for SwiGLU) -> [M, N] (or [M, F]); b_blocked: arb_pack_k_blocked(b)."""
     _dev(a, torch.bfloat16), _dev(b, torch.bfloat16)
+    if b_blocked is not None and (_dev(b_blocked, torch.bfloat16).numel() != b.numel() or a.shape[1] % 32):
+        raise ValueError("b_blocked does not match b")
     M, K = a.shape
     N = b.shape[0] // 2 if epilogue == ARB_EPI_SWIGLU_BF16 else b.shape[0]
     if b.shape[1] != K:
@@ -343,8 +356,20 @@ def arb_stage_gemm(a: torch.Tensor, b: torch.Tensor, epilogue: int = ARB_EPI_STO
     _dev(out, torch.float32 if epilogue in (ARB_EPI_RESIDUAL_F32, ARB_EPI_STORE_F32) else torch.bfloat16)
     if tuple(out.shape) != (M, N):
         raise ValueError("output shape")
-    _check(load_library().arb_stage_gemm(_ptr(a), _ptr(b), _ptr(out), M, N, K, epilogue, _stream(stream)))
+    _check(load_library().arb_stage_gemm(_ptr(a), _ptr(b), _ptr(b_blocked) if b_blocked is not None else None,
+                                         _ptr(out), M, N, K, epilogue, _stream(stream)))
     return out
+
+
+def arb_pack_k_blocked(w: torch.Tensor, stream=None) -> torch.Tensor:
+    """bf16 [rows, K] -> its K-blocked copy, bf16 [K/32, rows, 32]."""
+    _dev(w, torch.bfloat16)
+    rows, K = w.shape
+    if K % 32:
+        raise ValueError("K must be a multiple of 32")
+    packed = torch.empty(K // 32, rows, 32, dtype=torch.bfloat16, device=w.device)
+    _check(load_library().arb_pack_k_blocked(_ptr(w), rows, K, _ptr(packed), _stream(stream)))
+    return packed
 
 
 def arb_w4_quantize(w: torch.Tensor, stream=None):

@@ -31,6 +31,7 @@ struct arb_model {
   const bf16 *embed;
   std::vector<const bf16 *> wqkv, wo, wgu, wd;              // packed uint32 when w4
   std::vector<const bf16 *> sqkv, so, sgu, sd;              // group scales of 4-bit weights
+  std::vector<const bf16 *> wgu_blocked;                    // K-blocked copies of wgu (empty: none)
   bool w4 = false;
   std::vector<const float *> g_attn, g_mlp;
   const float *g_final, *w_head;
@@ -96,6 +97,13 @@ extern "C" arb_status arb_model_create(const arb_model_cfg *cfg, const arb_weigh
     }
     m->g_attn.push_back(w->g_attn[l]);
     m->g_mlp.push_back(w->g_mlp[l]);
+    if (w->wgu_blocked) {
+      if (!w->wgu_blocked[l] || m->w4 || c.d_model % 32 != 0) {
+        delete m;
+        return arb_fail(ARB_EINVAL, "arb_model_create: wgu_blocked needs bf16 weights and a pointer for every layer (layer %d)", l);
+      }
+      m->wgu_blocked.push_back((const bf16 *)w->wgu_blocked[l]);
+    }
   }
   m->g_final = w->g_final;
   m->w_head = c.has_router_head ? w->w_head : nullptr;
@@ -260,8 +268,8 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
   if (sq < 2) sq = 1;
   // one projection: bf16 weights, or packed 4-bit weights with their group scales
   auto project = [&](const bf16 *a, const bf16 *wt, const bf16 *scale, void *out, int N, int K, int epi, int splits,
-                     int part) {
-    if (!m->w4) return launch_gemm(a, wt, out, T, N, K, epi, st, splits, part);
+                     int part, const bf16 *wt_blocked = nullptr) {
+    if (!m->w4) return launch_gemm(a, wt, out, T, N, K, epi, st, splits, part, wt_blocked);
     if (part == GEMM_PART_SMALL) return (arb_status)ARB_OK;            // the 4-bit kernel is one launch
     return launch_gemm_w4(a, (const uint32_t *)wt, scale, out, T, N, K, epi, st, splits);
   };
@@ -316,7 +324,8 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
       TraceScope t(m, ARB_STAGE_GATE_UP, st);
       {
         TraceScope large(m, ARB_STAGE_GATE_UP_LARGE, st);
-        s = project(w.x, m->wgu[l], scale_of(m->sgu, l), w.act, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, 1, GEMM_PART_LARGE);
+        s = project(w.x, m->wgu[l], scale_of(m->sgu, l), w.act, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, 1, GEMM_PART_LARGE,
+                    m->wgu_blocked.empty() ? nullptr : m->wgu_blocked[l]);
       }
       if (!s) s = project(w.x, m->wgu[l], scale_of(m->sgu, l), w.act, c.d_ffn, d, ARB_EPI_SWIGLU_BF16, 1, GEMM_PART_SMALL);
     }
@@ -430,11 +439,18 @@ extern "C" arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block,
 
 // ------------------------------------------------------------------------- stages
 
-extern "C" arb_status arb_stage_gemm(const void *A, const void *B, void *C, int32_t M, int32_t N, int32_t K,
-                                     int32_t epilogue, void *stream) {
+extern "C" arb_status arb_stage_gemm(const void *A, const void *B, const void *B_blocked, void *C, int32_t M,
+                                     int32_t N, int32_t K, int32_t epilogue, void *stream) {
   if (M == 0) return ARB_OK;
   if (!A || !B || !C) return arb_fail(ARB_EINVAL, "arb_stage_gemm: null pointer");
-  return launch_gemm((const bf16 *)A, (const bf16 *)B, C, M, N, K, epilogue, (hipStream_t)stream);
+  return launch_gemm((const bf16 *)A, (const bf16 *)B, C, M, N, K, epilogue, (hipStream_t)stream, 1, GEMM_PART_ALL,
+                     (const bf16 *)B_blocked);
+}
+
+extern "C" arb_status arb_pack_k_blocked(const void *W, int64_t rows, int32_t K, void *packed, void *stream) {
+  if (rows < 0) return arb_fail(ARB_EINVAL, "arb_pack_k_blocked: rows = %lld", (long long)rows);
+  if (rows > 0 && (!W || !packed)) return arb_fail(ARB_EINVAL, "arb_pack_k_blocked: null pointer");
+  return launch_pack_k_blocked((const bf16 *)W, (size_t)rows, K, (bf16 *)packed, (hipStream_t)stream);
 }
 
 extern "C" arb_status arb_w4_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream) {

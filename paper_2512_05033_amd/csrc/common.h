@@ -73,8 +73,10 @@ static __device__ __forceinline__ void tile_of(int logical, int tiles_m, int til
 // A launch is up to two kernels: n-tile columns [0, gemm_large_cols) in 256x256 tiles, the rest in
 // 128x128 tiles; `part` restricts the call to one of them.
 enum { GEMM_PART_ALL = 0, GEMM_PART_LARGE = 1, GEMM_PART_SMALL = 2 };
+// B_blocked: optional K-blocked copy of B (launch_pack_k_blocked); the 256x256-tile part of the launch reads it instead of B.
 arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st,
-                       int splits = 1, int part = GEMM_PART_ALL);
+                       int splits = 1, int part = GEMM_PART_ALL, const bf16 *B_blocked = nullptr);
+arb_status launch_pack_k_blocked(const bf16 *W, size_t rows, int K, bf16 *packed, hipStream_t st);
 int gemm_large_cols(int M, int N, int K, int epilogue, int splits);   // in units of 256 columns (128 SwiGLU features)
 int gemm_residual_splits(int M, int N, int K);
 

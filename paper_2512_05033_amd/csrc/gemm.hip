@@ -428,7 +428,9 @@ constexpr int LM = 256, LN = 256, LK = 32;
 constexpr int L_TILE = LM * LK;          // elements per operand and stage
 
 
-template <int EPI>
+// BLOCKED: B is the K-blocked copy of the weights, [K/32][rows][32] (arb_pack_k_blocked): the 16 rows of a
+// wave-wide load of one K step are then 1 KB of consecutive memory, whole cache lines, instead of 16 half lines.
+template <int EPI, bool BLOCKED>
 __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                          void *__restrict__ Cv, int M, int N, int K, int tiles_m,
                                                          int tiles_n) {
@@ -458,8 +460,11 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
   // r/128, MFMA tile (r%128)/32 (even = gate, odd = up) and feature offset r%32, i.e. feature
   // tile_n*128 + (r/64)*32 + r%32 of the gate (r/32 even) or up (odd) half; N = F there.
   const int b_row0 = EPI == ARB_EPI_SWIGLU_BF16 ? tile_n * 128 + (row0 & 31) + ((row0 >> 5) & 1) * N : tile_n * LN + row0;
-  const size_t b_step = (size_t)(EPI == ARB_EPI_SWIGLU_BF16 ? 32 : 64) * K;
-  const bf16 *b_src = B + (size_t)b_row0 * K + chunk * 8;
+  const size_t b_rows = EPI == ARB_EPI_SWIGLU_BF16 ? 2 * (size_t)N : (size_t)N;      // rows of the weight matrix
+  const size_t b_row_pitch = BLOCKED ? 32 : (size_t)K;                                  // elements between rows
+  const size_t b_k_pitch = BLOCKED ? b_rows * 32 : (size_t)LK;                          // elements between K steps
+  const size_t b_step = (size_t)(EPI == ARB_EPI_SWIGLU_BF16 ? 32 : 64) * b_row_pitch;
+  const bf16 *b_src = B + (size_t)b_row0 * b_row_pitch + chunk * 8;
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -481,7 +486,7 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
   auto dma_b = [&](int s, int kt) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src + i * b_step + (size_t)kt * LK), LDS_PTR(ARB_STAGE(Bs, s) + (i * 4 + wave_u) * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(b_src + i * b_step + (size_t)kt * b_k_pitch), LDS_PTR(ARB_STAGE(Bs, s) + (i * 4 + wave_u) * 512), 16, 0, 0);
   };
   bf16x8 fa[2][4], fb[2][4];
   // Fragment reads in the order the MFMAs (row-major over the 4x4 tiles) first need them.
@@ -636,7 +641,7 @@ int gemm_large_cols(int M, int N, int K, int epilogue, int splits) {
 }
 
 arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int K, int epilogue, hipStream_t st,
-                       int splits, int part) {
+                       int splits, int part, const bf16 *B_blocked) {
   if (M == 0) return ARB_OK;
   if (M < 0 || N <= 0 || K <= 0) return arb_fail(ARB_EINVAL, "gemm: M=%d N=%d K=%d", M, N, K);
   if (K % BK != 0) return arb_fail(ARB_EUNSUPPORTED, "gemm: K=%d is not a multiple of %d", K, BK);
@@ -656,7 +661,13 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   if (big_cols > 0 && part != GEMM_PART_SMALL) {
     const int tm = ceil_div(M, LM);
     const dim3 bgrid(tm * big_cols), bblock(256);
-#define ARB_BIG(E) hipLaunchKernelGGL((gemm256_kernel<E>), bgrid, bblock, 0, st, A, B, C, M, N, K, tm, big_cols)
+#define ARB_BIG(E)                                                                                                     \
+  do {                                                                                                                 \
+    if (B_blocked)                                                                                                     \
+      hipLaunchKernelGGL((gemm256_kernel<E, true>), bgrid, bblock, 0, st, A, B_blocked, C, M, N, K, tm, big_cols);     \
+    else                                                                                                               \
+      hipLaunchKernelGGL((gemm256_kernel<E, false>), bgrid, bblock, 0, st, A, B, C, M, N, K, tm, big_cols);            \
+  } while (0)
     switch (epilogue) {
       case ARB_EPI_STORE_BF16: ARB_BIG(ARB_EPI_STORE_BF16); break;
       case ARB_EPI_RESIDUAL_F32: ARB_BIG(ARB_EPI_RESIDUAL_F32); break;
@@ -702,5 +713,26 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   }
 #undef ARB_SMALL
   ARB_CHECK_LAUNCH("gemm");
+  return ARB_OK;
+}
+
+// packed[(kb * rows + r) * 32 + j] = W[r][kb * 32 + j]: one thread per 16-byte chunk
+__global__ __launch_bounds__(256) void pack_k_blocked_kernel(const bf16 *__restrict__ W, size_t rows, int K,
+                                                             bf16 *__restrict__ packed) {
+  const size_t chunks_per_row = K / 8, total = rows * chunks_per_row;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t r = i / chunks_per_row, c = i - r * chunks_per_row;      // source row and 16-byte chunk
+    const size_t kb = c / 4;
+    *(bf16x8 *)(packed + (kb * rows + r) * 32 + (c % 4) * 8) = *(const bf16x8 *)(W + r * (size_t)K + c * 8);
+  }
+}
+
+arb_status launch_pack_k_blocked(const bf16 *W, size_t rows, int K, bf16 *packed, hipStream_t st) {
+  if (rows == 0) return ARB_OK;
+  if (K <= 0 || K % 32 != 0) return arb_fail(ARB_EUNSUPPORTED, "pack_k_blocked: K=%d is not a multiple of 32", K);
+  const size_t chunks = rows * (size_t)(K / 8);
+  const int blocks = (int)((chunks + 255) / 256 < 8192 ? (chunks + 255) / 256 : 8192);
+  hipLaunchKernelGGL(pack_k_blocked_kernel, dim3(blocks), dim3(256), 0, st, W, rows, K, packed);
+  ARB_CHECK_LAUNCH("pack_k_blocked");
   return ARB_OK;
 }

@@ -76,6 +76,16 @@ def test_model_create_validation(lib):
     assert _create(lib, _cfg(), wn)[0] == B.ARB_EINVAL
     assert _create(lib, _cfg(has_router_head=0), wn)[0] == B.ARB_OK
     assert lib.arb_model_create(None, None, None) == B.ARB_EINVAL
+    # optional K-blocked gate/up copies: one pointer per layer or none at all
+    wb, keep_b = _weights()
+    wb.wgu_blocked = keep_b
+    assert _create(lib, _cfg(), wb)[0] == B.ARB_OK
+    holes = (C.c_void_p * 2)(0x1000, None)
+    wb.wgu_blocked = holes
+    assert _create(lib, _cfg(), wb)[0] == B.ARB_EINVAL and b"wgu_blocked" in lib.arb_last_error()
+    assert lib.arb_pack_k_blocked(0x1000, 4, 48, 0x1000, None) == B.ARB_EUNSUPPORTED       # K % 32
+    assert lib.arb_pack_k_blocked(None, 4, 64, 0x1000, None) == B.ARB_EINVAL
+    assert lib.arb_pack_k_blocked(None, 0, 64, None, None) == B.ARB_OK
 
 
 def test_batch_validation_happens_on_the_host(lib):
@@ -110,8 +120,8 @@ def test_batch_validation_happens_on_the_host(lib):
     assert lib.arb_budget_threshold(0x1000, -1, 0, 0x1000, None) == B.ARB_EINVAL
     assert lib.arb_budget_threshold(0x1000, 4, 1, None, None) == B.ARB_EINVAL
     assert lib.arb_stage_layers(None, None, None, 0, 1, None, None, None, 0, None) == B.ARB_EINVAL
-    assert lib.arb_stage_gemm(0x1000, 0x1000, 0x1000, 8, 128, 96, 0, None) == B.ARB_EUNSUPPORTED
-    assert lib.arb_stage_gemm(0x1000, 0x1000, 0x1000, 8, 100, 128, 0, None) == B.ARB_EUNSUPPORTED
+    assert lib.arb_stage_gemm(0x1000, 0x1000, None, 0x1000, 8, 128, 96, 0, None) == B.ARB_EUNSUPPORTED
+    assert lib.arb_stage_gemm(0x1000, 0x1000, None, 0x1000, 8, 100, 128, 0, None) == B.ARB_EUNSUPPORTED
     lib.arb_model_destroy(h)
 
 

@@ -91,6 +91,30 @@ def test_gemm_swiglu(A, M, F, K):
     assert got.shape == (M, F) and rel_err(bf16_np(got), ref) < 5e-3
 
 
+@pytest.mark.parametrize("rows,K", [(1, 32), (130, 96), (17920, 1536)])
+def test_pack_k_blocked_bit_exact(A, rows, K):
+    w = rand_bf16((rows, K), 1.0, 21)
+    want = W.bf16_bits(w).reshape(rows, K // 32, 32).transpose(1, 0, 2)       # [K/32][rows][32]
+    assert np.array_equal(W.bf16_bits(A.arb_pack_k_blocked(w)), want)
+
+
+@pytest.mark.parametrize("M,N,K,epi", [(4000, 8960, 1536, "swiglu"), (3300, 2048, 128, "swiglu"), (2000, 8960, 128, "swiglu"),
+                                       (3300, 4096, 256, "store"), (4000, 8960, 128, "store"),
+                                       (130, 64, 128, "swiglu")])          # no large tiles: the copy is not read
+def test_gemm_from_k_blocked_weights_is_bit_identical(A, M, N, K, epi):
+    """The large-tile kernel reading the K-blocked copy does the same arithmetic in the same order."""
+    swiglu = epi == "swiglu"
+    a, b = rand_bf16((M, K), 1.0, 13), rand_bf16(((2 if swiglu else 1) * N, K), 0.05, 14)
+    e = A.ARB_EPI_SWIGLU_BF16 if swiglu else A.ARB_EPI_STORE_BF16
+    assert (A.arb_gemm_large_tile_columns(M, N, K, e) > 0) == (M > 1000)
+    plain = A.arb_stage_gemm(a, b, e)
+    blocked = A.arb_stage_gemm(a, b, e, b_blocked=A.arb_pack_k_blocked(b))
+    assert np.array_equal(W.bf16_bits(plain), W.bf16_bits(blocked))
+    af, bf = bf16_np(a), bf16_np(b)
+    ref = O.silu(af @ bf[:N].T) * (af @ bf[N:].T) if swiglu else af @ bf.T
+    assert rel_err(bf16_np(blocked), ref) < 5e-3
+
+
 def test_gemm_rejects_unsupported_shapes(A):
     a, b = rand_bf16((8, 96), 1.0, 1), rand_bf16((128, 96), 1.0, 2)
     with pytest.raises(A.ArbError) as e:
@@ -395,6 +419,24 @@ def test_c2_two_layers_full_batch(A):
     _assert_scores(sess.batch, scores, esc, s_ref, e_ref)
     slots = O.slot_mapping(sess.batch.prefix_lens, sess.batch.cu_step_lens, sess.batch.block_tables, 16)
     _assert_cache(sess, kp, vp, kp_before, slots)
+
+
+def test_c2_two_layers_without_k_blocked_weights_is_bit_identical(A):
+    """A model created without the optional K-blocked gate/up copy gives the same bits as one with it."""
+    h = H()
+    w = W.scaled(W.C2, n_layers=2)
+    sess = h.setup(w, "cuda", gain_jitter=0.1)
+    out = []
+    for block in (True, False):
+        m = w.model
+        model = A.Model(n_layers=m.n_layers, d_model=m.d_model, n_q_heads=m.n_q_heads, n_kv_heads=m.n_kv_heads,
+                        head_dim=m.head_dim, d_ffn=m.d_ffn, vocab=m.vocab, weights=sess.weights, rms_eps=m.rms_eps,
+                        rope_base=m.rope_base, kv_block=m.kv_block, block_gate_up=block)
+        scores, esc, hidden = A.arb_score_steps(model, sess.kv, sess.dbatch, sess.batch.tau, want_hidden=True, ws=sess.ws)
+        torch.cuda.synchronize()
+        out.append((scores.cpu().numpy(), W.bf16_bits(hidden)))
+        model.close()
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
 
 
 def _full_batch_sampled(A, w, pick, *, gain_jitter=0.1, hidden_tol=HIDDEN_TOL):
