@@ -21,8 +21,8 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # Counter runs of the dominant kernel on workload C2 (profiles/score_steps_C2_hbm_traffic.txt): scaled
 # FETCH_SIZE + WRITE_SIZE bytes per launch, and the SHA-256 of the csrc/gemm.hip they were taken with.
-COUNTED_GATE_UP_BYTES = 75765665 + 16777216
-COUNTED_GEMM_SHA256 = "4087d989fdc51d83d158cef81f68ae558f36e86957e621ae1f8927def421f662"
+COUNTED_GATE_UP_BYTES = 75765729 + 16777216
+COUNTED_GEMM_SHA256 = "8a57723c0ac3adf4ecfcf291ec4fa046460046a5545222969886a9ea3c9c0d54"
 
 
 def cpu_baseline(w, sess, layers: int):
@@ -108,7 +108,7 @@ def main():
     large_cols = A.arb_gemm_large_tile_columns(T, F, d, A.ARB_EPI_SWIGLU_BF16)
     if large_cols > 0:
         gu_stage, gu_features = A.ARB_STAGE_GATE_UP_LARGE, large_cols * 128
-        gu_kernel = f"gemm256_kernel<SWIGLU> (gate/up projection, features [0, {gu_features}) of {F} in 256x256 tiles)"
+        gu_kernel = f"gemm256_kernel<SWIGLU, K-blocked weights> (gate/up projection, features [0, {gu_features}) of {F} in 256x256 tiles)"
     else:
         gu_stage, gu_features = A.ARB_STAGE_GATE_UP, F
         gu_kernel = "gemm_kernel<SWIGLU> (gate/up projection, 128x128 tiles)"
