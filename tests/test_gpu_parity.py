@@ -313,6 +313,12 @@ def _attention_case(A, shape, prefix, steps, peaky, seed):
     (W.ROUTER_1P5B, [300, 77, 1000, 0, 2048], [5, 64, 33, 20, 1]),      # G=6, ragged, empty prefix, decode row
     (W.TARGET_8B, [4096, 15, 4097], [64, 1, 128]),                       # G=4, 2 query tiles, several splits
     (W.TINY, [512, 3, 130], [32, 64, 7]),                                # head_dim 64
+    # sequences of the 256-row kernel (more than 128 rows per kv head, an even number of 128-row tiles or seven
+    # and more): one to five key tiles (the four-stage ring wraps), an empty prefix, a last tile of 129 rows,
+    # next to sequences of the 128-row kernel (3 and 5 tiles of 128 rows, a decode row) in the same call
+    (W.TINY, [0, 40, 200, 700, 100, 64, 9], [128, 96, 100, 130, 65, 190, 1]),       # head_dim 64, G=2
+    (W.TARGET_8B, [0, 60, 130, 250, 2000], [33, 64, 64, 240, 129]),      # G=4: 132, 256, 256, 960, 516 rows
+    (W.ROUTER_1P5B, [10, 5000, 333], [40, 150, 64]),                     # G=6: 240, 900 rows; 384 rows (128-row kernel)
 ])
 def test_attention_stage(A, shape, prefix, steps, peaky):
     got, ref = _attention_case(A, shape, prefix, steps, peaky, 31)
