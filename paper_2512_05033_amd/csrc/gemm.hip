@@ -474,7 +474,13 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = K / LK, last = nk - 1;
+  // K range of this workgroup (the whole of K unless the launch is split along K), in pairs of steps
+  const int pairs_all = K / (2 * LK);
+  const int kt_begin = 2 * (int)((long long)pairs_all * blockIdx.y / gridDim.y);
+  const int nk = 2 * (int)((long long)pairs_all * (blockIdx.y + 1) / gridDim.y) - kt_begin, last = nk - 1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_src[i] += (size_t)kt_begin * LK;
+  b_src += (size_t)kt_begin * b_k_pitch;
   const int frag_row = lane & 31, frag_half = lane >> 5;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 #define ARB_STAGE(base, s) ((s) == 0 ? base##0 : (s) == 1 ? base##1 : (s) == 2 ? base##2 : base##3)
@@ -601,8 +607,8 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
           if (m < M) {
             if (EPI == ARB_EPI_STORE_BF16) {
               ((bf16 *)Cv)[(size_t)m * N + col] = (bf16)acc[i][j][r];
-            } else if (EPI == ARB_EPI_STORE_F32) {
-              ((float *)Cv)[(size_t)m * N + col] = acc[i][j][r];
+            } else if (EPI == EPI_PARTIAL_F32) {
+              ((float *)Cv)[((size_t)blockIdx.y * M + m) * N + col] = acc[i][j][r];
             } else {
               float *dst = (float *)Cv + (size_t)m * N + col;
               *dst += acc[i][j][r];
@@ -615,7 +621,23 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
 
 }  // namespace
 
+// K splits of a projection with fp32 partial products that runs in 256x256 tiles: few token rows
+// (M a little above a multiple of 128 wastes most of a 128-row tile row) and a long K, where 128x128 tiles would
+// be a single under-filled round (more than 256 of them, so no deep-ring kernel either).  0: not such a launch.
+static int gemm_large_splits(int M, int N, int K) {
+  if (M <= 0 || N <= 0 || N % LN != 0 || K < 2048) return 0;
+  const int tiles_small = ceil_div(M, BM) * (N / BN), tm256 = ceil_div(M, 256);
+  if (tiles_small <= 256 || 512 / tiles_small > 1) return 0;                     // ring kernels / split small tiles
+  if (tm256 * (N / BN) >= 192 && tm256 * (N / BN) <= 256) return 0;              // one round of 256x128 ring tiles
+  const int tiles = ceil_div(M, LM) * (N / LN);
+  int s = 256 / tiles;
+  if (s > K / (16 * LK)) s = K / (16 * LK);                                       // at least 16 steps per split
+  if (s > 8) s = 8;
+  return s >= 2 && tiles * s >= 205 ? s : 0;
+}
+
 int gemm_residual_splits(int M, int N, int K) {
+  if (const int s = gemm_large_splits(M, N, K)) return s;
   // as many workgroups as are resident at once (two per CU on 256 CUs) without starting a second
   // round, each keeping at least 4 K-steps; the partials cost 8 bytes of traffic per element and
   // split, so no more splits than that (measured on the 1.5B shape: 5 beats 4 and 6 for K = 8960).
@@ -632,8 +654,10 @@ int gemm_large_cols(int M, int N, int K, int epilogue, int splits) {
   // Large tiles run one per CU, so they go in whole rounds of 256: as many n-tile columns as fill whole
   // rounds (all of them when the last round would be at least 80 % full), the remaining columns in
   // 128x128 tiles.  With less than one round of large tiles everything runs in small ones.
-  (void)K;
   const int big_n = epilogue == ARB_EPI_SWIGLU_BF16 ? 128 : LN;       // a large n-tile is two small ones
+  if (splits > 1 && (epilogue == ARB_EPI_RESIDUAL_F32 || epilogue == ARB_EPI_STORE_F32) &&
+      splits == gemm_large_splits(M, N, K))
+    return N / LN;                                                     // split-K partial products in large tiles
   if (splits != 1 || M <= 0 || N <= 0 || N % big_n != 0) return 0;
   const int tm = ceil_div(M, LM), tn = N / big_n, total = tm * tn, tail = total % 256;
   if (total < 205) return 0;
@@ -660,7 +684,7 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   const int big_cols = gemm_large_cols(M, N, K, epilogue, splits);   // n-tile columns given to the large-tile kernel
   if (big_cols > 0 && part != GEMM_PART_SMALL) {
     const int tm = ceil_div(M, LM);
-    const dim3 bgrid(tm * big_cols), bblock(256);
+    const dim3 bgrid(tm * big_cols, splits), bblock(256);
 #define ARB_BIG(E)                                                                                                     \
   do {                                                                                                                 \
     if (B_blocked)                                                                                                     \
@@ -670,7 +694,9 @@ arb_status launch_gemm(const bf16 *A, const bf16 *B, void *C, int M, int N, int 
   } while (0)
     switch (epilogue) {
       case ARB_EPI_STORE_BF16: ARB_BIG(ARB_EPI_STORE_BF16); break;
-      case ARB_EPI_RESIDUAL_F32: ARB_BIG(ARB_EPI_RESIDUAL_F32); break;
+      case ARB_EPI_RESIDUAL_F32:
+        if (splits > 1) ARB_BIG(EPI_PARTIAL_F32); else ARB_BIG(ARB_EPI_RESIDUAL_F32);
+        break;
       case ARB_EPI_STORE_F32: ARB_BIG(ARB_EPI_STORE_F32); break;
       case ARB_EPI_SWIGLU_BF16: ARB_BIG(ARB_EPI_SWIGLU_BF16); break;
       default: return arb_fail(ARB_EINVAL, "gemm: unknown epilogue %d", epilogue);
