@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
     const bf16 *__restrict__ q, int q_row_stride, const bf16 *__restrict__ k_pool, const bf16 *__restrict__ v_pool,
     const int32_t *__restrict__ block_tables, int max_blocks, const int32_t *__restrict__ prefix_lens,
     const int32_t *__restrict__ cu, int T, int Hq, int Hkv, int max_qtiles, int max_splits, int kv_chunk,
-    float scale_log2, bf16 *__restrict__ out, bf16 *__restrict__ part_acc, float *__restrict__ part_ml) {
+    float scale_log2, bf16 *__restrict__ out, bf16 *__restrict__ part_acc, float *__restrict__ part_ml, int n_groups) {
   constexpr int CPK = HD / 8;              // 16-byte chunks per key
   constexpr int LOADS = KT * CPK / 256;    // wave-wide 1 KB loads per wave, operand and tile
   constexpr int KPL = 64 / CPK;            // keys covered by one wave-wide load (4 or 8: inside one block)
@@ -165,19 +165,20 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
   // behind the direct-to-LDS loads in flight into the other.
   __shared__ __attribute__((aligned(16))) bf16 K0[KT * HD], K1[KT * HD], V0[KT * HD], V1[KT * HD];
 
-  // Work item of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a
-  // contiguous range of items, ordered so that the query tiles that stream the same keys (same
-  // sequence, kv head and split) are neighbours and meet in that XCD's L2.
-  int item;
-  {
-    const int total = gridDim.x, per = total / 8, rem = total % 8;
-    const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
-    item = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + j;
-  }
-  const int qtile = item % max_qtiles; item /= max_qtiles;
-  const int split = item % max_splits; item /= max_splits;
-  const int hk = item % Hkv;
-  const int b = item / Hkv;
+  // Work item of this workgroup.  The hardware deals workgroups round-robin to the 8 XCDs (blockIdx % 8), and
+  // an XCD works through its share in order.  The query tiles of one group (sequence, split, kv head) stream the
+  // same keys: they stay on one XCD, next to each other in its order, and meet in its L2.  The groups are dealt
+  // round-robin with the kv head as the fastest index, then the split: consecutive groups are equally long, so
+  // every XCD gets the same share of every sequence.  (With a contiguous range of sequences per XCD the XCD
+  // with the longest ones finished last: on 16 contexts of 5 K to 32 K keys only 59 % of the workgroup slots
+  // were busy on average, 75 % with this order.)
+  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+  const int qtile = slot % max_qtiles;
+  int item = (slot / max_qtiles) * 8 + xcd;                 // group index
+  if (item >= n_groups) return;
+  const int hk = item % Hkv; item /= Hkv;
+  const int split = item % max_splits;
+  const int b = item / max_splits;
   const int G = Hq / Hkv;
   const int p = prefix_lens[b], tok0 = cu[b], s = cu[b + 1] - tok0;
   const int rows = s * G, row0 = qtile * QROWS;
@@ -431,11 +432,12 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
     }
   }
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)head_dim));
-  const dim3 grid(batch * n_kv_heads * plan.max_splits * plan.max_qtiles), block(256);
+  const int n_groups = batch * n_kv_heads * plan.max_splits;      // (sequence, split, kv head)
+  const dim3 grid(ceil_div(n_groups, 8) * 8 * plan.max_qtiles), block(256);
 #define ARB_ATTN_LAUNCH(HD, SPLIT)                                                                                 \
   hipLaunchKernelGGL((attention_kernel<HD, SPLIT>), grid, block, 0, st, q, q_row_stride, k_pool, v_pool,           \
                      block_tables, max_blocks_per_seq, prefix_lens, cu_step_lens, total_tokens, n_q_heads,         \
-                     n_kv_heads, plan.max_qtiles, plan.max_splits, plan.kv_chunk, scale_log2, out, part_acc, part_ml)
+                     n_kv_heads, plan.max_qtiles, plan.max_splits, plan.kv_chunk, scale_log2, out, part_acc, part_ml, n_groups)
   if (head_dim == 128) { if (split) ARB_ATTN_LAUNCH(128, true); else ARB_ATTN_LAUNCH(128, false); }
   else                 { if (split) ARB_ATTN_LAUNCH(64, true);  else ARB_ATTN_LAUNCH(64, false); }
 #undef ARB_ATTN_LAUNCH
