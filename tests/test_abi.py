@@ -125,6 +125,36 @@ def test_batch_validation_happens_on_the_host(lib):
     lib.arb_model_destroy(h)
 
 
+def test_launch_plan_of_the_projection_gemm_is_host_arithmetic(lib):
+    """arb_gemm_large_tile_columns: whole rounds of 256 large tiles go to the large-tile kernel, the rest
+    (or everything, when there is less than a round) to small tiles."""
+    from paper_2512_05033_amd import binding as B
+    cols = lambda M, N, K, e: lib.arb_gemm_large_tile_columns(M, N, K, e)
+    # C2 gate/up: 4 x 70 large tiles -> one round of 4 x 64, 6 columns (768 features) left to small tiles
+    assert cols(1024, 8960, 1536, B.ARB_EPI_SWIGLU_BF16) == 64
+    # less than 205 large tiles: small tiles only
+    assert cols(130, 64, 128, B.ARB_EPI_SWIGLU_BF16) == 0
+    assert cols(1024, 2048, 1536, B.ARB_EPI_STORE_BF16) == 0
+    # 13 x 16 = 208 large tiles: one round, at least 80 % full -> all 16 columns
+    assert cols(3300, 4096, 256, B.ARB_EPI_STORE_BF16) == 16
+    # 16 x 35 = 560: two rounds = 32 columns, the other 3 columns in small tiles
+    assert cols(4000, 8960, 128, B.ARB_EPI_STORE_BF16) == 32
+    # a width that is not a multiple of the large tile never uses it; bad sizes give 0
+    assert cols(4000, 8960 + 128, 128, B.ARB_EPI_STORE_BF16) == 0
+    assert cols(0, 4096, 256, B.ARB_EPI_STORE_BF16) == 0 and cols(-5, 4096, 256, B.ARB_EPI_STORE_BF16) == 0
+
+
+def test_workspace_size_grows_with_every_argument(lib):
+    w, _keep = _weights()
+    st, h = _create(lib, _cfg(), w)
+    base = lib.arb_workspace_bytes(h, 4, 128, 544)
+    assert base > 0 and base % 256 == 0
+    assert lib.arb_workspace_bytes(h, 4, 256, 544) > base
+    assert lib.arb_workspace_bytes(h, 4, 128, 40000) > base            # more key splits to merge
+    assert lib.arb_workspace_bytes(h, 4, 0, 0) >= 0
+    lib.arb_model_destroy(h)
+
+
 def test_binding_refuses_to_run_without_the_library(tmp_path):
     from paper_2512_05033_amd import binding
     with pytest.raises(RuntimeError, match="no fallback"):
