@@ -551,7 +551,7 @@ __global__ __launch_bounds__(256, 1) void gemm256_kernel(const bf16 *__restrict_
   dma_a(0, 0); dma_b(0, 0);
   dma_a(1, min(1, last)); dma_b(1, min(1, last));
   dma_a(2, min(2, last)); dma_b(2, min(2, last));
-  __builtin_amdgcn_s_waitcnt(0x0070);       // vmcnt(0) lgkmcnt(0)
+  __builtin_amdgcn_s_waitcnt(0x4070);       // vmcnt(16) lgkmcnt(0): step 0 has landed, steps 1 and 2 may be in flight
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_sched_barrier(0);
   frags(0, 0, 0);
