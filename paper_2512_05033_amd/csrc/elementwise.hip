@@ -250,7 +250,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv
   const float *prow = PARTS ? parts + (size_t)j * n_heads * hd : nullptr;
   const int slot = tok_slot[j];
   const size_t blk = slot / ARB_KV_BLOCK, off = slot % ARB_KV_BLOCK;
-  for (int u = threadIdx.x; u < n_heads * units_per_head; u += blockDim.x) {
+  // one unit per thread: blockIdx.y walks the units of the token in groups of 256, so that a token's row is
+  // one round of memory latency whatever its width (a loop over the units took one round per 256 of them,
+  // 6 rounds per token on the 8B shape: most of the kernel's time in small batches)
+  const int u = blockIdx.y * blockDim.x + threadIdx.x;
+  if (u < n_heads * units_per_head) {
     const int head = u / units_per_head, t = (u - head * units_per_head) * 2;
     bf16 *src = row + head * hd;
     float a[2], b[2];
@@ -293,11 +297,12 @@ arb_status launch_rope_append(bf16 *qkv, const float *parts, int n_parts, const 
                               hipStream_t st) {
   if (T == 0) return ARB_OK;
   const size_t stride = (size_t)T * (n_q_heads + 2 * n_kv_heads) * head_dim;
+  const dim3 grid(T, ceil_div((n_q_heads + 2 * n_kv_heads) * (head_dim / 4), 256));
   if (n_parts > 0)
-    hipLaunchKernelGGL((rope_append_kernel<true>), dim3(T), dim3(256), 0, st, qkv, parts, n_parts, stride, cs, tok_slot,
+    hipLaunchKernelGGL((rope_append_kernel<true>), grid, dim3(256), 0, st, qkv, parts, n_parts, stride, cs, tok_slot,
                        k_pool, v_pool, n_q_heads, n_kv_heads, head_dim);
   else
-    hipLaunchKernelGGL((rope_append_kernel<false>), dim3(T), dim3(256), 0, st, qkv, (const float *)nullptr, 0, stride, cs,
+    hipLaunchKernelGGL((rope_append_kernel<false>), grid, dim3(256), 0, st, qkv, (const float *)nullptr, 0, stride, cs,
                        tok_slot, k_pool, v_pool, n_q_heads, n_kv_heads, head_dim);
   ARB_CHECK_LAUNCH("rope_append");
   return ARB_OK;
