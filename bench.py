@@ -71,8 +71,8 @@ def main():
                          "that hardware-counter runs are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU (sequences are independent; see DESIGN.md for how the path "
-                 "would shard); run with --gpus 1")
+        sys.exit("bench.py: this library runs on one GPU (sequences are independent, so a batch would shard by "
+                 "sequence across GPUs with no communication on the path); run with --gpus 1")
 
     import torch
 
