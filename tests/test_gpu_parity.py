@@ -328,6 +328,21 @@ def test_attention_stage(A, shape, prefix, steps, peaky):
     assert row_err.max() < 3e-2
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_attention_stage_random_ragged_batches(A, seed):
+    """Seeded random batch sizes, prefixes and step lengths (grids whose group count is not a multiple of
+    the 8 XCDs, empty prefixes, one-token steps next to multi-tile steps) on the three head shapes."""
+    rng = np.random.default_rng(1000 + seed)
+    shape = (W.TINY, W.ROUTER_1P5B, W.TARGET_8B, W.ROUTER_1P5B)[seed % 4]
+    n = int(rng.integers(1, 10))
+    prefix = [int(v) for v in rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 300, 700, 1500, 2600], size=n)]
+    steps = [int(v) for v in rng.choice([1, 2, 5, 16, 21, 22, 33, 43, 64, 70], size=n)]
+    got, ref = _attention_case(A, shape, prefix, steps, False, 50 + seed)
+    assert rel_err(got, ref) < 1e-2
+    row_err = np.abs(got - ref).max(axis=-1) / (np.abs(ref).max(axis=-1) + 1e-3)
+    assert row_err.max() < 3e-2
+
+
 # ---------------------------------------------------------------------- end to end
 
 def _oracle_run(sess, pool_mode="mean"):
