@@ -342,17 +342,39 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const bf16 *__rest
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-#pragma unroll 2
-  for (int sidx = 0; sidx < n_splits; ++sidx) {
-    const float2 ml = *(const float2 *)(part_ml + (sidx * stride + idx) * 2);
-    const bf16x8 v = *(const bf16x8 *)(part_acc + (sidx * stride + idx) * HD + piece * 8);
-    if (ml.x == -INFINITY) continue;                       // no key of this split is visible to the row
-    const float m_new = fmaxf(m, ml.x);
-    const float keep = exp2f(m - m_new), w = exp2f(ml.x - m_new) * ml.y;
-    m = m_new;
-    l = l * keep + w;
+  // Splits are taken eight at a time: all their loads go out together (a loop over a run-time count waits for
+  // each before it asks for the next), then they are combined under their common maximum; groups of eight are
+  // chained by the usual online rescaling.
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+    float2 ml[8];
+    bf16x8 v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = acc[e] * keep + w * (float)v[e];
+    for (int j = 0; j < 8; ++j) {
+      if (s0 + j < n_splits) {
+        ml[j] = *(const float2 *)(part_ml + ((s0 + j) * stride + idx) * 2);
+        v[j] = *(const bf16x8 *)(part_acc + ((s0 + j) * stride + idx) * HD + piece * 8);
+      } else {
+        ml[j] = float2{-INFINITY, 0.f};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[j][e] = (bf16)0.f;
+      }
+    }
+    float m_new = m;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m_new = fmaxf(m_new, ml[j].x);
+    if (m_new == -INFINITY) continue;                      // no key of these splits is visible to the row
+    const float keep = exp2f(m - m_new);                   // m = -inf: 0
+    m = m_new;
+    l *= keep;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= keep;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float w = exp2f(ml[j].x - m_new) * ml[j].y;    // a split without visible keys: exp2(-inf) * 0 = 0
+      l += w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += w * (float)v[j][e];
+    }
   }
   const float inv = 1.0f / l;
   bf16x8 r;
