@@ -78,7 +78,7 @@ def main():
 
     import paper_2512_05033_amd as A
     import workloads as W
-    from paper_2512_05033_amd import harness
+    import harness
 
     A.load_library()
     torch.cuda.set_device(0)

@@ -28,6 +28,13 @@
  *    not advancing prefix_lens; accepting it (x <- x || z) is advancing it by s_b.
  *    Repeating a call with the same arguments gives the same results.
  *
+ * Debug mode: if the environment variable ARB_DEBUG_IDS is set (to anything but "0") when arb_model_create
+ * runs, every arb_prefill / arb_score_steps / arb_stage_layers call of that model
+ * first range-checks, on the device, the token ids against [0, vocab) and every block id its sequences
+ * reference against [0, arb_kv.n_blocks), waits for the result (the one case in which a hot call
+ * synchronises) and returns ARB_EINVAL naming the first offender before any kernel has used an id.
+ * Without it ids are trusted: a bad one is an out-of-bounds access.
+ *
  * Supported shapes: head_dim == 64 or 128; d_model, d_ffn and n_q_heads*head_dim multiples of
  * 128; n_q_heads a multiple of n_kv_heads; kv_block == 16.  Others -> ARB_EUNSUPPORTED.
  */

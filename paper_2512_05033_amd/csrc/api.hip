@@ -6,6 +6,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include <new>
 #include <vector>
@@ -33,6 +34,7 @@ struct arb_model {
   std::vector<const bf16 *> sqkv, so, sgu, sd;              // group scales of 4-bit weights
   std::vector<const bf16 *> wgu_blocked;                    // K-blocked copies of wgu (empty: none)
   bool w4 = false;
+  bool debug_ids = false;                                 // ARB_DEBUG_IDS: range-check ids before every forward
   std::vector<const float *> g_attn, g_mlp;
   const float *g_final, *w_head;
   float b_head;
@@ -83,6 +85,8 @@ extern "C" arb_status arb_model_create(const arb_model_cfg *cfg, const arb_weigh
   if (!m) return arb_fail(ARB_EINVAL, "arb_model_create: out of host memory");
   m->cfg = c;
   m->w4 = n_scale == 4;
+  const char *dbg = getenv("ARB_DEBUG_IDS");
+  m->debug_ids = dbg && dbg[0] && dbg[0] != '0';
   m->embed = (const bf16 *)w->embed;
   for (int l = 0; l < c.n_layers; ++l) {
     m->wqkv.push_back((const bf16 *)w->wqkv[l]);
@@ -159,7 +163,8 @@ struct Workspace {
   size_t attn_ws_bytes, total;
 };
 
-static Workspace carve(const arb_model_cfg &c, int T, int max_ctx, void *base) {
+// attn_splits: the number of key splits whose partial results the attention part must hold.
+static Workspace carve(const arb_model_cfg &c, int T, int attn_splits, void *base) {
   Workspace w;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -178,7 +183,7 @@ static Workspace carve(const arb_model_cfg &c, int T, int max_ctx, void *base) {
   w.cs = (f32x2 *)take(t * (c.head_dim / 2) * sizeof(f32x2));
   w.tok_dot = (float *)take(t * sizeof(float));
   w.parts = (float *)take(8 * t * c.d_model * sizeof(float));
-  w.attn_ws_bytes = attention_ws_bytes(attention_splits_cap(max_ctx), T, c.n_q_heads, c.head_dim);
+  w.attn_ws_bytes = attention_ws_bytes(attn_splits, T, c.n_q_heads, c.head_dim);
   w.attn_ws = take(w.attn_ws_bytes);
   w.total = off;
   return w;
@@ -187,7 +192,7 @@ static Workspace carve(const arb_model_cfg &c, int T, int max_ctx, void *base) {
 extern "C" size_t arb_workspace_bytes(const arb_model *m, int32_t max_batch, int32_t max_total_tokens,
                                       int32_t max_ctx) {
   if (!m || max_batch < 0 || max_total_tokens < 0 || max_ctx < 0) return 0;
-  return carve(m->cfg, max_total_tokens, max_ctx, nullptr).total;
+  return carve(m->cfg, max_total_tokens, attention_splits_cap(max_ctx), nullptr).total;
 }
 
 // --------------------------------------------------------------- batch validation
@@ -246,12 +251,31 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
   for (int l = l0; l < l1; ++l)
     if (!kv->k_pool[l] || !kv->v_pool[l]) return arb_fail(ARB_EINVAL, "null kv pool in layer %d", l);
   const int T = bt->total_tokens, B = bt->batch, d = c.d_model;
-  const Workspace w = carve(c, T, info.max_ctx, ws);
-  if (!ws || ws_bytes < w.total) return arb_fail(ARB_ECAPACITY, "workspace %zu < %zu bytes", ws_bytes, w.total);
-  if (h_in) ARB_CHECK_HIP(hipMemcpyAsync(w.h, h_in, (size_t)T * d * sizeof(float), hipMemcpyDeviceToDevice, st));
-
   const int G = c.n_q_heads / c.n_kv_heads;
   const AttnPlan plan = plan_attention(B, bt->prefix_lens_host, bt->cu_step_lens_host, G, c.n_kv_heads);
+  // the attention part is sized by this call's own split count (never above what arb_workspace_bytes assumed)
+  const Workspace w = carve(c, T, plan.max_splits, ws);
+  if (!ws || ws_bytes < w.total) return arb_fail(ARB_ECAPACITY, "workspace %zu < %zu bytes", ws_bytes, w.total);
+  if (m->debug_ids) {
+    // Debug mode (environment variable ARB_DEBUG_IDS at arb_model_create): the ids the kernels would
+    // index with are range-checked on the device first, and this call waits for the verdict, so that a
+    // bad id becomes an error instead of an out-of-bounds access.  The error word borrows the
+    // workspace's partial-product area, which nothing has written yet.
+    if (kv->n_blocks <= 0) return arb_fail(ARB_EINVAL, "debug id check: arb_kv.n_blocks = %d", kv->n_blocks);
+    int32_t *err = (int32_t *)w.parts, host[4] = {0, 0, 0, 0};
+    if (arb_status s0 = launch_check_ids(h_in ? nullptr : bt->token_ids, T, c.vocab, bt->block_tables, B,
+                                         bt->max_blocks_per_seq, bt->prefix_lens, bt->cu_step_lens, c.kv_block,
+                                         kv->n_blocks, err, st))
+      return s0;
+    ARB_CHECK_HIP(hipMemcpyAsync(host, err, sizeof host, hipMemcpyDeviceToHost, st));
+    ARB_CHECK_HIP(hipStreamSynchronize(st));
+    if (host[0] & 1)
+      return arb_fail(ARB_EINVAL, "debug id check: token_ids[%d] is outside [0, %d)", host[1], c.vocab);
+    if (host[0] & 2)
+      return arb_fail(ARB_EINVAL, "debug id check: block_tables[%d][%d] is outside [0, %d)",
+                      host[2] / bt->max_blocks_per_seq, host[2] % bt->max_blocks_per_seq, kv->n_blocks);
+  }
+  if (h_in) ARB_CHECK_HIP(hipMemcpyAsync(w.h, h_in, (size_t)T * d * sizeof(float), hipMemcpyDeviceToDevice, st));
 
   // The residual projections (O, down) are split along K when their N is too narrow to fill the
   // chip; their fp32 products (one per split; a single one when not split: a plain store is cheaper

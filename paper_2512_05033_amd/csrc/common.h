@@ -99,6 +99,10 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
 arb_status launch_token_meta(const int32_t *prefix_lens, const int32_t *cu_step_lens, const int32_t *block_tables,
                              int batch, int total_tokens, int max_blocks_per_seq, int kv_block, int32_t *tok_pos,
                              int32_t *tok_slot, hipStream_t st);
+// Debug range check of token ids and of the block ids a batch references; err: device int32 [4].
+arb_status launch_check_ids(const int32_t *token_ids, int T, int vocab, const int32_t *block_tables, int batch,
+                            int max_blocks_per_seq, const int32_t *prefix_lens, const int32_t *cu_step_lens,
+                            int kv_block, int n_blocks, int32_t *err, hipStream_t st);
 arb_status launch_rope_table(const int32_t *tok_pos, int total_tokens, int head_dim, float rope_base, f32x2 *cs,
                              hipStream_t st);
 arb_status launch_embed_rmsnorm(const bf16 *embed, const int32_t *token_ids, const float *g, float eps, int T, int d,

@@ -52,6 +52,57 @@ arb_status launch_token_meta(const int32_t *prefix_lens, const int32_t *cu_step_
   return ARB_OK;
 }
 
+// ------------------------------------------------------------- debug: id range check
+
+// err[0]: bit 0 = a token id outside [0, vocab), bit 1 = a referenced block id outside [0, n_blocks);
+// err[1] / err[2]: smallest offending index into token_ids / block_tables (INT32_MAX: none).
+__global__ void check_ids_init_kernel(int32_t *err) {
+  err[0] = 0;
+  err[1] = err[2] = INT32_MAX;
+  err[3] = 0;
+}
+
+// One thread per token id, then one per block-table entry.  Entry j of row b is referenced iff
+// j < ceil((p_b + s_b) / blk); the rest of a row may hold anything.
+__global__ void check_ids_kernel(const int32_t *__restrict__ token_ids, int T, int vocab,
+                                 const int32_t *__restrict__ tables, int batch, int max_blocks,
+                                 const int32_t *__restrict__ prefix_lens, const int32_t *__restrict__ cu, int blk,
+                                 int n_blocks, int32_t *err) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < T) {
+    if (token_ids) {
+      const int id = token_ids[i];
+      if (id < 0 || id >= vocab) {
+        atomicOr(&err[0], 1);
+        atomicMin(&err[1], (int)i);
+      }
+    }
+    return;
+  }
+  const long long e = i - T;
+  if (e >= (long long)batch * max_blocks) return;
+  const int b = (int)(e / max_blocks), j = (int)(e - (long long)b * max_blocks);
+  const int ctx = prefix_lens[b] + cu[b + 1] - cu[b];
+  if (j >= (ctx + blk - 1) / blk) return;
+  const int id = tables[e];
+  if (id < 0 || id >= n_blocks) {
+    atomicOr(&err[0], 2);
+    atomicMin(&err[2], (int)e);
+  }
+}
+
+arb_status launch_check_ids(const int32_t *token_ids, int T, int vocab, const int32_t *block_tables, int batch,
+                            int max_blocks_per_seq, const int32_t *prefix_lens, const int32_t *cu_step_lens,
+                            int kv_block, int n_blocks, int32_t *err, hipStream_t st) {
+  hipLaunchKernelGGL(check_ids_init_kernel, dim3(1), dim3(1), 0, st, err);
+  ARB_CHECK_LAUNCH("check_ids_init");
+  const long long n = (long long)T + (long long)batch * max_blocks_per_seq;
+  hipLaunchKernelGGL(check_ids_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, token_ids, T, vocab,
+                     block_tables, batch, max_blocks_per_seq, prefix_lens, cu_step_lens, kv_block, n_blocks, err);
+  ARB_CHECK_LAUNCH("check_ids");
+  return ARB_OK;
+}
+
 // -------------------------------------------------------------------- rotary table
 
 // cs[j][t] = (cos, sin) of pos_j * base^(-2t/hd), evaluated in fp64 so that the

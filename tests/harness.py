@@ -11,7 +11,7 @@ import torch
 
 import workloads as W
 
-from . import binding as A
+import paper_2512_05033_amd as A
 
 
 @dataclass

@@ -410,6 +410,49 @@ def test_zero_projections_reduce_to_identity():
     assert np.allclose(y, ref, atol=1e-12)
 
 
+def test_decoder_layers_is_the_forward_without_its_ends_and_ranges_compose():
+    """decoder_layers referees the per-layer GPU checks, so it is pinned here: over all layers it is
+    forward() before the final norm (same bits, same cache); the stream it keeps after layer l is the
+    one a model cut off after l + 1 layers normalises; consecutive ranges compose bit for bit."""
+    from dataclasses import replace
+    deep = replace(SMALL, n_layers=3)
+    wl = replace(SMALL_W, model=deep)
+    batch = W.make_batch(wl)
+    weights = W.make_weights(deep, wl.seed, sigma=0.3, gain_jitter=0.1)
+    m, p = oracle_model(deep), oracle_params(weights)
+    pools = lambda: oracle_pools(*W.make_kv_pools(wl, batch))
+    args = (batch.prefix_lens, batch.cu_step_lens, batch.block_tables)
+    kp0, vp0 = pools()
+    y = O.forward(m, p, kp0, vp0, batch.token_ids, *args)
+    kp1, vp1 = pools()
+    h0 = O.embed(p.embed, batch.token_ids)
+    keep = []
+    h = O.decoder_layers(m, p, kp1, vp1, h0, 0, 3, *args, keep=keep)
+    assert len(keep) == 3 and keep[-1] is h
+    assert np.array_equal(O.rmsnorm(h, p.g_final, deep.rms_eps), y)
+    for l in range(3):
+        assert np.array_equal(kp0[l], kp1[l]) and np.array_equal(vp0[l], vp1[l])
+    # the kept stream after layer l, against a model that ends there
+    for l in range(3):
+        cut = replace(deep, n_layers=l + 1)
+        kpc, vpc = pools()
+        yc = O.forward(oracle_model(cut), p, kpc, vpc, batch.token_ids, *args)
+        assert np.array_equal(O.rmsnorm(keep[l], p.g_final, deep.rms_eps), yc)
+        assert not np.array_equal(keep[l], keep[l - 1] if l else h0)
+    # [0, 1) then [1, 3) is [0, 3); a range touches only its own layers' cache
+    kp2, vp2 = pools()
+    fresh = [a.copy() for a in kp2]
+    mid = O.decoder_layers(m, p, kp2, vp2, h0, 0, 1, *args)
+    assert np.array_equal(mid, keep[0])
+    assert np.array_equal(kp2[1], fresh[1]) and np.array_equal(kp2[2], fresh[2]) and not np.array_equal(kp2[0], fresh[0])
+    end = O.decoder_layers(m, p, kp2, vp2, mid, 1, 3, *args)
+    assert np.array_equal(end, h)
+    for l in range(3):
+        assert np.array_equal(kp2[l], kp1[l]) and np.array_equal(vp2[l], vp1[l])
+    # an empty range is the identity
+    assert np.array_equal(O.decoder_layers(m, p, kp2, vp2, h0, 2, 2, *args), h0)
+
+
 def test_fp32_weights_are_the_bf16_values():
     """Params given as widened floats or as bf16 bits are the same model."""
     batch, weights = small_case()
