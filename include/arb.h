@@ -29,7 +29,7 @@
  *    Repeating a call with the same arguments gives the same results.
  *
  * Debug mode: if the environment variable ARB_DEBUG_IDS is set (to anything but "0") when arb_model_create
- * runs, every arb_prefill / arb_score_steps / arb_stage_layers call of that model
+ * runs, every arb_prefill / arb_score_steps / arb_score_steps_noalloc / arb_stage_layers call of that model
  * first range-checks, on the device, the token ids against [0, vocab) and every block id its sequences
  * reference against [0, arb_kv.n_blocks), waits for the result (the one case in which a hot call
  * synchronises) and returns ARB_EINVAL naming the first offender before any kernel has used an id.
@@ -163,6 +163,20 @@ size_t arb_workspace_bytes(const arb_model *m, int32_t max_batch, int32_t max_to
  * in every layer's pool.  batch == 0 is a no-op. */
 arb_status arb_score_steps(arb_model *m, const arb_kv *kv, const arb_batch *batch, float tau, float *scores,
                            uint8_t *escalate, void *hidden_out, void *ws, size_t ws_bytes, void *stream);
+
+/* arb_score_steps for callers that cannot allocate or hold a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and results (bit for bit) without `ws`:
+ * the workspace is a static device array of ARB_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU
+ * the library runs on, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine); its first call on a device looks the array's address up (not stream work; do
+ * it once before capturing).  A batch whose workspace would exceed the array returns ARB_ECAPACITY with a
+ * message that says how much it needs (the array holds e.g. 128 step tokens of the 1.5B-class shape
+ * against 32 K contexts, or 64 of the 8B-class shape against 8 K); arb_workspace_bytes is an upper bound of
+ * that need.  All calls on one GPU share the array: calls that overlap on one GPU (different streams or
+ * threads) race; calls on one stream do not.  Nothing in it has to be cleared between calls. */
+#define ARB_NOALLOC_SCRATCH_BYTES (64u << 20)
+arb_status arb_score_steps_noalloc(arb_model *m, const arb_kv *kv, const arb_batch *batch, float tau, float *scores,
+                                   uint8_t *escalate, void *hidden_out, void *stream);
 
 /* Fills the cache for whole prompts: the same forward with the "step" being the
  * prompt (prefix_lens normally all 0; a non-zero prefix continues a chunked

@@ -25,7 +25,9 @@ ARB_EPI_STORE_BF16, ARB_EPI_RESIDUAL_F32, ARB_EPI_SWIGLU_BF16, ARB_EPI_STORE_F32
  ARB_STAGE_ROPE_APPEND, ARB_STAGE_GATE_UP_LARGE) = range(8)
 _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4: "ARB_EHIP", 5: "ARB_EUNSUPPORTED"}
 
-EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_prefill",
+NOALLOC_SCRATCH_BYTES = 64 << 20      # ARB_NOALLOC_SCRATCH_BYTES of include/arb.h
+
+EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_score_steps_noalloc", "arb_prefill",
            "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_pack_k_blocked", "arb_w4_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
            "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
@@ -79,6 +81,8 @@ def load_library(path: Optional[str] = None):
     lib.arb_model_destroy.argtypes = [C.c_void_p]
     lib.arb_score_steps.argtypes = [C.c_void_p, C.POINTER(_KV), C.POINTER(_Batch), C.c_float, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_score_steps_noalloc.argtypes = [C.c_void_p, C.POINTER(_KV), C.POINTER(_Batch), C.c_float, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p]
     lib.arb_prefill.argtypes = [C.c_void_p, C.POINTER(_KV), C.POINTER(_Batch), C.c_void_p, C.c_void_p, C.c_size_t,
                                 C.c_void_p]
     lib.arb_route.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p]
@@ -259,6 +263,15 @@ def arb_score_steps(model: Model, kv: KVCache, batch: DeviceBatch, tau: float, *
     ws = _workspace(model, batch, ws)
     _check(load_library().arb_score_steps(model.handle, C.byref(kv.c), C.byref(batch.c), float(tau), _ptr(scores),
                                           _ptr(escalate), _ptr(hidden), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return scores, escalate, hidden
+
+
+def arb_score_steps_noalloc(model: Model, kv: KVCache, batch: DeviceBatch, tau: float, *, scores=None, escalate=None,
+                            hidden=None, stream=None):
+    """arb_score_steps on the library's static scratch buffer.  The caller passes every output tensor
+    (scores and escalate when the model has a head; hidden optional); nothing is allocated here."""
+    _check(load_library().arb_score_steps_noalloc(model.handle, C.byref(kv.c), C.byref(batch.c), float(tau),
+                                                  _ptr(scores), _ptr(escalate), _ptr(hidden), _stream(stream)))
     return scores, escalate, hidden
 
 

@@ -8,6 +8,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -239,7 +240,8 @@ static arb_status check_batch(const arb_batch *bt, int kv_block, BatchInfo *info
 // residual stream after layer l1 - 1 back through h_out, with no final norm.
 static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, bool with_head, float tau,
                           float *scores, uint8_t *escalate, void *hidden_out, void *ws, size_t ws_bytes,
-                          hipStream_t st, int l0, int l1, const float *h_in = nullptr, float *h_out = nullptr) {
+                          hipStream_t st, int l0, int l1, const float *h_in = nullptr, float *h_out = nullptr,
+                          bool ws_is_static = false) {
   if (!m || !kv) return arb_fail(ARB_EINVAL, "null model or kv");
   const arb_model_cfg &c = m->cfg;
   BatchInfo info;
@@ -255,6 +257,9 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
   const AttnPlan plan = plan_attention(B, bt->prefix_lens_host, bt->cu_step_lens_host, G, c.n_kv_heads);
   // the attention part is sized by this call's own split count (never above what arb_workspace_bytes assumed)
   const Workspace w = carve(c, T, plan.max_splits, ws);
+  if (ws_is_static && ws_bytes < w.total)
+    return arb_fail(ARB_ECAPACITY, "arb_score_steps_noalloc: this batch needs %zu bytes of scratch but the static buffer "
+                    "holds %zu (ARB_NOALLOC_SCRATCH_BYTES); use arb_score_steps with a workspace", w.total, ws_bytes);
   if (!ws || ws_bytes < w.total) return arb_fail(ARB_ECAPACITY, "workspace %zu < %zu bytes", ws_bytes, w.total);
   if (m->debug_ids) {
     // Debug mode (environment variable ARB_DEBUG_IDS at arb_model_create): the ids the kernels would
@@ -386,6 +391,44 @@ extern "C" arb_status arb_score_steps(arb_model *m, const arb_kv *kv, const arb_
   if (!m) return arb_fail(ARB_EINVAL, "null model");
   return forward(m, kv, batch, m->cfg.has_router_head != 0, tau, scores, escalate, hidden_out, ws, ws_bytes,
                  (hipStream_t)stream, 0, m->cfg.n_layers);
+}
+
+// ---- the entry point that allocates nothing: the workspace is a static device array ----
+
+// Every GPU the library runs on holds its own copy of this array (at its own address) until the process
+// ends.  In host code the name is only a handle for hipGetSymbolAddress: kernels and copies get the
+// per-device address resolved below, never the name.
+static __device__ __align__(256) unsigned char scratch[ARB_NOALLOC_SCRATCH_BYTES];
+
+static const int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, once resolved
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch`, looked up once per device.
+static arb_status static_scratch(void **out) {
+  int dev = -1;
+  ARB_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return arb_fail(ARB_EUNSUPPORTED, "arb_score_steps_noalloc: device index %d", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    ARB_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return arb_fail(ARB_EHIP, "arb_score_steps_noalloc: the static scratch buffer has no address on device %d", dev);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return ARB_OK;
+}
+
+extern "C" arb_status arb_score_steps_noalloc(arb_model *m, const arb_kv *kv, const arb_batch *batch, float tau,
+                                              float *scores, uint8_t *escalate, void *hidden_out, void *stream) {
+  if (!m) return arb_fail(ARB_EINVAL, "null model");
+  void *ws = nullptr;
+  if (arb_status s = static_scratch(&ws)) return s;
+  // Nothing in the workspace is read before this call has written it (every buffer is a kernel's output
+  // before it is another's input), so the previous call's contents need no clearing.
+  return forward(m, kv, batch, m->cfg.has_router_head != 0, tau, scores, escalate, hidden_out, ws,
+                 ARB_NOALLOC_SCRATCH_BYTES, (hipStream_t)stream, 0, m->cfg.n_layers, nullptr, nullptr, true);
 }
 
 extern "C" arb_status arb_prefill(arb_model *m, const arb_kv *kv, const arb_batch *batch, void *hidden_out, void *ws,
