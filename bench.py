@@ -2,8 +2,13 @@
 
 A step = one arb_score_steps call (embedding, L transformer layers of
 append-attention + projections, final norm, pooled router head, threshold) over
-one batch of the 1.5B-router-shaped workload (16 sequences, 2048-token cached
-prefix, 64-token drafted step), inputs resident in HBM.  Prints one JSON line.
+one batch of a synthetic workload, inputs resident in HBM.  The headline line is
+the 1.5B-router-shaped workload C2 (16 sequences, 2048-token cached prefix,
+64-token drafted step); `per_config` carries the same measurements for every
+full-size workload (C2..C5): step time, scored step-tokens/s, append-attention
+GB/s and its fraction of HBM peak, per-projection and aggregate GEMM TFLOP/s and
+their fraction of the bf16 MFMA peak, the whole step against its roofline, and
+the CPU oracle timed on a bounded sample.  Prints one JSON line.
 """
 import argparse
 import hashlib
@@ -24,10 +29,34 @@ PEAK_HBM_GBS = 8000.0
 COUNTED_GATE_UP_BYTES = 75791902 + 16777216
 COUNTED_GEMM_SHA256 = "b92d31b84caa34adf6078b6498e96b8c33086020f1e92ebbd1713c867cefe0f5"
 
+# Which sequences the CPU oracle recomputes per workload (the rungs of the stated ladder): the whole batch
+# where that takes seconds, else a seeded sub-batch at full depth that includes the extremes.
+CPU_SAMPLE = {"C2": "all", "C3": "all", "C4": 8, "C5": 4}
 
-def cpu_baseline(w, sess, layers: int):
-    """The CPU oracle, as it stands, on a bounded sample: the full batch through
-    the first `layers` layers plus final norm and head; scaled to full depth."""
+
+def _pick(name, batch):
+    import numpy as np
+    kind = CPU_SAMPLE.get(name, "all")
+    if kind == "all":
+        return list(range(batch.batch))
+    if name == "C5":     # shortest and longest prefix of each step kind (even: 1 token, odd: 64)
+        dec, big = np.arange(0, batch.batch, 2), np.arange(1, batch.batch, 2)
+        return sorted({int(dec[np.argmin(batch.prefix_lens[dec])]), int(dec[np.argmax(batch.prefix_lens[dec])]),
+                       int(big[np.argmin(batch.prefix_lens[big])]), int(big[np.argmax(batch.prefix_lens[big])])})
+    pick = {int(np.argmin(batch.prefix_lens)), int(np.argmax(batch.prefix_lens)),
+            int(np.argmin(batch.step_lens)), int(np.argmax(batch.step_lens))}
+    for b in np.random.default_rng(0).permutation(batch.batch):
+        if len(pick) >= kind:
+            break
+        pick.add(int(b))
+    return sorted(pick)
+
+
+def cpu_baseline(name, w, sess, layers: int):
+    """The CPU oracle, as it stands, on a bounded sample of the workload: the sequences of _pick through
+    the first `layers` layers (all of them by default) plus final norm and head; the time is scaled to
+    full depth when fewer layers ran.  The cache blocks those sequences reference are copied from the
+    device as bf16 bit patterns."""
     import numpy as np
     import torch
     from threadpoolctl import threadpool_info
@@ -36,26 +65,152 @@ def cpu_baseline(w, sess, layers: int):
     from helpers import oracle_model, oracle_params
     from oracle import arb_oracle as O
 
-    sub = W.scaled(w, n_layers=layers)
+    batch, L = sess.batch, w.model.n_layers
+    pick = _pick(name, batch)
+    sub = batch.select(pick)
+    need = (sub.prefix_lens + sub.step_lens + 15) // 16
+    used = np.concatenate([sub.block_tables[i, :need[i]] for i in range(sub.batch)])
+    remap = -np.ones(batch.n_blocks, np.int64); remap[used] = np.arange(len(used))
+    tables = np.where(np.arange(sub.block_tables.shape[1])[None, :] < need[:, None], remap[sub.block_tables], 0)
+    idx = torch.as_tensor(used, dtype=torch.int64, device="cuda")
+    kp = [W.bf16_bits(sess.kv.k_pools[l][idx]).copy() for l in range(layers)]
+    vp = [W.bf16_bits(sess.kv.v_pools[l][idx]).copy() for l in range(layers)]
     wt = sess.weights
     cpu = lambda t: t.cpu()
     weights = W.Weights(cpu(wt.embed), [cpu(t) for t in wt.wqkv[:layers]], [cpu(t) for t in wt.wo[:layers]],
                         [cpu(t) for t in wt.wgu[:layers]], [cpu(t) for t in wt.wd[:layers]],
                         [cpu(t) for t in wt.g_attn[:layers]], [cpu(t) for t in wt.g_mlp[:layers]], cpu(wt.g_final),
                         cpu(wt.w_head), wt.b_head)
-    m, p = oracle_model(sub.model), oracle_params(weights)
-    batch = sess.batch
-    kp = [W.bf16_bits(sess.kv.k_pools[l]).copy() for l in range(layers)]
-    vp = [W.bf16_bits(sess.kv.v_pools[l]).copy() for l in range(layers)]
+    m, p = oracle_model(W.scaled(w, n_layers=layers).model), oracle_params(weights)
     t0 = time.perf_counter()
-    O.score_steps(m, p, kp, vp, batch.token_ids, batch.prefix_lens, batch.cu_step_lens, batch.block_tables, batch.tau)
+    y = O.forward(m, p, kp, vp, sub.token_ids, sub.prefix_lens, sub.cu_step_lens, tables)
+    if w.model.has_router_head:
+        O.route(O.router_scores(y, sub.cu_step_lens, p.w_head, p.b_head), batch.tau)
     dt = time.perf_counter() - t0
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
-    full = dt * w.model.n_layers / layers
-    return {"value": batch.total_tokens / full, "unit": "scored step-tokens/s", "cores": int(threads),
-            "kind": "oracle",
-            "sample": f"full batch ({batch.batch} seq, {batch.total_tokens} step tokens) through the first {layers} of "
-                      f"{w.model.n_layers} layers + head in {dt:.1f} s; value = tokens / (time x {w.model.n_layers}/{layers})"}
+    full = dt * L / layers
+    what = f"all {batch.batch} sequences" if len(pick) == batch.batch else \
+        f"{len(pick)} of {batch.batch} sequences (shortest/longest prefix and step among them)"
+    depth = f"all {L} layers" if layers == L else f"the first {layers} of {L} layers, time x {L}/{layers}"
+    return {"value": sub.total_tokens / full, "unit": "scored step-tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{what}, {sub.total_tokens} step tokens against {int(sub.prefix_lens.sum())} cached tokens, "
+                      f"{depth}, + final norm and head: {dt:.1f} s"}
+
+
+STAGES = ("qkv", "attention", "oproj", "gate_up", "down", "norm", "rope_append")
+
+
+def run_config(name, steps, warmup, cpu_layers, copy_probe_mib=0):
+    """Sets one workload up on the device, times `steps` calls after `warmup`, then (outside the timed
+    region) times every stage with the library's event hook and runs the CPU sample."""
+    import torch
+
+    import harness
+    import paper_2512_05033_amd as A
+    import workloads as W
+
+    w = W.ALL[name]
+    sess = harness.setup(w, "cuda")
+    batch, model, m = sess.batch, sess.model, w.model
+    T, L, d, F = batch.total_tokens, m.n_layers, m.d_model, m.d_ffn
+    head = m.has_router_head
+    scores = torch.empty(batch.batch, dtype=torch.float32, device="cuda") if head else None
+    esc = torch.empty(batch.batch, dtype=torch.uint8, device="cuda") if head else None
+    hidden = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        A.arb_score_steps(model, sess.kv, sess.dbatch, batch.tau, ws=sess.ws, scores=scores, escalate=esc,
+                          hidden=hidden)
+
+    if copy_probe_mib > 0:
+        src = torch.arange(copy_probe_mib << 18, dtype=torch.float32, device="cuda")   # 4 bytes each
+        torch.empty_like(src).copy_(src)
+        del src
+    for _ in range(warmup):
+        step()
+    # The gate/up projection's dominant kernel is bracketed by HIP events inside the library, on the stream
+    # it runs on, during the timed steps: the kernel with the SwiGLU epilogue, or, where the projection is
+    # launched as two kernels, the 256x256-tile kernel that does most of its columns.
+    large_cols = A.arb_gemm_large_tile_columns(T, F, d, A.ARB_EPI_SWIGLU_BF16)
+    if large_cols > 0:
+        gu_stage, gu_features = A.ARB_STAGE_GATE_UP_LARGE, large_cols * 128
+        gu_kernel = f"gemm256_kernel<SWIGLU, K-blocked weights> (gate/up projection, features [0, {gu_features}) of {F} in 256x256 tiles)"
+    else:
+        gu_stage, gu_features = A.ARB_STAGE_GATE_UP, F
+        gu_kernel = "gemm_kernel<SWIGLU> (gate/up projection, 128x128 tiles)"
+    timer = A.StageTimer(model, gu_stage, steps * L)
+    timer.arm()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n = timer.disarm()
+    gu_ms = timer.durations_ms(n)
+    timer.close()
+    ms_per_step = dt / steps * 1e3
+    gu_avg_ms = sum(gu_ms) / len(gu_ms)
+    gu_flops = 2.0 * T * (2 * gu_features) * d                            # per launch of that kernel
+    gu_achieved = gu_flops / (gu_avg_ms * 1e-3) / 1e12
+
+    # per-stage times: extra passes, outside the timed region
+    ids = {"qkv": A.ARB_STAGE_QKV, "attention": A.ARB_STAGE_ATTENTION, "oproj": A.ARB_STAGE_OPROJ,
+           "gate_up": A.ARB_STAGE_GATE_UP, "down": A.ARB_STAGE_DOWN, "norm": A.ARB_STAGE_NORM,
+           "rope_append": A.ARB_STAGE_ROPE_APPEND}
+    reps, stage_ms = 3, {}
+    for sname in STAGES:
+        t = A.StageTimer(model, ids[sname], reps * L)
+        t.arm()
+        for _ in range(reps):
+            step()
+        torch.cuda.synchronize()
+        dur = t.durations_ms(t.disarm())
+        t.close()
+        stage_ms[sname] = sum(dur) / reps
+    # algorithmic work of one layer
+    ctx = (batch.prefix_lens + batch.step_lens).astype(float)
+    s, p = batch.step_lens.astype(float), batch.prefix_lens.astype(float)
+    kv_bytes = float((ctx * 2 * m.n_kv_heads * m.head_dim * 2).sum())
+    qo_bytes = 2.0 * T * m.n_q_heads * m.head_dim * 2
+    attn_flops = float((4 * m.n_q_heads * m.head_dim * (s * p + s * (s + 1) / 2)).sum())
+    gemm_flops = {"qkv": 2.0 * T * m.qkv_rows * d, "oproj": 2.0 * T * d * m.n_q_heads * m.head_dim,
+                  "gate_up": 2.0 * T * 2 * F * d, "down": 2.0 * T * d * F}
+    weight_bytes = 2.0 * m.params_per_layer
+    attn_s = stage_ms["attention"] / L * 1e-3
+    attn_bound_s = max((kv_bytes + qo_bytes) / (PEAK_HBM_GBS * 1e9), attn_flops / (PEAK_BF16_TFLOPS * 1e12))
+    gemm_s = sum(stage_ms[k] for k in gemm_flops) / L * 1e-3
+    gemm_bound_s = max(sum(gemm_flops.values()) / (PEAK_BF16_TFLOPS * 1e12), weight_bytes / (PEAK_HBM_GBS * 1e9))
+    roof_ms = (attn_bound_s + gemm_bound_s) * L * 1e3
+    entry = {
+        "workload": w.name, "layers": L, "d_model": d, "batch": batch.batch, "step_tokens": T,
+        "prefix_tokens": int(batch.prefix_lens.sum()), "kv": f"paged-16 {w.tables}", "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "step_tokens_per_s": T / (ms_per_step * 1e-3),
+        "step_roofline": {"ms": roof_ms, "frac": roof_ms / ms_per_step,
+                          "what": "per layer max(GEMM flop / bf16 peak, weight bytes / HBM peak) + max(attention bytes / HBM peak, attention flop / bf16 peak)"},
+        "stage_ms_per_step": stage_ms,
+        "attention": {"us_per_layer": attn_s * 1e6, "GBps": (kv_bytes + qo_bytes) / attn_s / 1e9,
+                      "hbm_frac": (kv_bytes + qo_bytes) / attn_s / 1e9 / PEAK_HBM_GBS,
+                      "TFLOPs": attn_flops / attn_s / 1e12, "mfma_frac": attn_flops / attn_s / 1e12 / PEAK_BF16_TFLOPS,
+                      "flop_per_byte": attn_flops / (kv_bytes + qo_bytes),
+                      "bound": "hbm" if (kv_bytes + qo_bytes) / (PEAK_HBM_GBS * 1e9) >= attn_flops / (PEAK_BF16_TFLOPS * 1e12) else "mfma",
+                      "frac_of_bound": attn_bound_s / attn_s},
+        "gemm": {"TFLOPs": {k: v / (stage_ms[k] / L * 1e-3) / 1e12 for k, v in gemm_flops.items()},
+                 "mfma_frac": {k: v / (stage_ms[k] / L * 1e-3) / 1e12 / PEAK_BF16_TFLOPS for k, v in gemm_flops.items()},
+                 "aggregate_TFLOPs": sum(gemm_flops.values()) / gemm_s / 1e12,
+                 "aggregate_mfma_frac": sum(gemm_flops.values()) / gemm_s / 1e12 / PEAK_BF16_TFLOPS,
+                 "dominant_kernel": {"kernel": gu_kernel, "avg_launch_ms": gu_avg_ms, "launches": n,
+                                     "flops_per_launch": gu_flops, "TFLOPs": gu_achieved,
+                                     "mfma_frac": gu_achieved / PEAK_BF16_TFLOPS}},
+    }
+    if cpu_layers != 0:
+        entry["cpu_baseline"] = cpu_baseline(name, w, sess, L if cpu_layers < 0 else min(cpu_layers, L))
+    model.close()
+    del sess, hidden, scores, esc
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    return entry
 
 
 def main():
@@ -63,9 +218,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--workload", default="C2", help="the workload of the headline value")
+    ap.add_argument("--configs", default="C2,C3,C4,C5", help="workloads reported in per_config (comma separated; '' = only the headline)")
     ap.add_argument("--cpu-layers", type=int, default=-1, help="layers of the oracle sample (-1 = all, 0 = skip the CPU baseline)")
-    ap.add_argument("--breakdown", action="store_true", help="also time each stage (extra passes, not in the timed region)")
+    ap.add_argument("--breakdown", action="store_true", help="kept for compatibility: stage times are always reported")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the warm-up, run one plain device copy of this many MiB (a kernel of known traffic "
                          "that hardware-counter runs are scaled by)")
@@ -77,104 +233,40 @@ def main():
     import torch
 
     import paper_2512_05033_amd as A
-    import workloads as W
-    import harness
 
     A.load_library()
     torch.cuda.set_device(0)
-    w = W.ALL[args.workload]
-    sess = harness.setup(w, "cuda")
-    batch, model = sess.batch, sess.model
-    T, L = batch.total_tokens, w.model.n_layers
-    head = w.model.has_router_head
-    scores = torch.empty(batch.batch, dtype=torch.float32, device="cuda") if head else None
-    esc = torch.empty(batch.batch, dtype=torch.uint8, device="cuda") if head else None
-    hidden = torch.empty(T, w.model.d_model, dtype=torch.bfloat16, device="cuda")
-
-    def step():
-        A.arb_score_steps(model, sess.kv, sess.dbatch, batch.tau, ws=sess.ws, scores=scores, escalate=esc,
-                          hidden=hidden)
-
-    if args.copy_probe_mib > 0:
-        src = torch.arange(args.copy_probe_mib << 18, dtype=torch.float32, device="cuda")   # 4 bytes each
-        torch.empty_like(src).copy_(src)
-        del src
-    for _ in range(args.warmup):
-        step()
-    # The dominant kernel is bracketed by HIP events inside the library, on the stream it runs on,
-    # during the timed steps: the gate/up projection with the SwiGLU epilogue, or, where that
-    # projection is launched as two kernels, the 256x256-tile kernel that does most of its columns.
-    F, d = w.model.d_ffn, w.model.d_model
-    large_cols = A.arb_gemm_large_tile_columns(T, F, d, A.ARB_EPI_SWIGLU_BF16)
-    if large_cols > 0:
-        gu_stage, gu_features = A.ARB_STAGE_GATE_UP_LARGE, large_cols * 128
-        gu_kernel = f"gemm256_kernel<SWIGLU, K-blocked weights> (gate/up projection, features [0, {gu_features}) of {F} in 256x256 tiles)"
-    else:
-        gu_stage, gu_features = A.ARB_STAGE_GATE_UP, F
-        gu_kernel = "gemm_kernel<SWIGLU> (gate/up projection, 128x128 tiles)"
-    timer = A.StageTimer(model, gu_stage, args.steps * L)
-    timer.arm()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    n = timer.disarm()
-    gu_ms = timer.durations_ms(n)
-    timer.close()
-    ms_per_step = dt / args.steps * 1e3
-    gu_avg_ms = sum(gu_ms) / len(gu_ms)
-    gu_flops = 2.0 * T * (2 * gu_features) * d                            # per launch of that kernel
-    achieved = gu_flops / (gu_avg_ms * 1e-3) / 1e12
+    names = [args.workload] + [c for c in args.configs.split(",") if c and c != args.workload]
+    per_config = []
+    for i, name in enumerate(names):
+        per_config.append(run_config(name, args.steps, args.warmup, args.cpu_layers,
+                                     args.copy_probe_mib if i == 0 else 0))
+        print(f"bench: {name} done: {per_config[-1]['ms_per_step']:.3f} ms per step", file=sys.stderr, flush=True)
+    per_config.sort(key=lambda e: e["workload"])
+    head = next(e for e in per_config if e["workload"].startswith(args.workload))
+    dom = head["gemm"]["dominant_kernel"]
     # HBM-side bytes per launch of that kernel from the FETCH_SIZE / WRITE_SIZE counter runs
     # (profiles/score_steps_C2_hbm_traffic.txt); only valid for the kernel source they were taken with
     traffic = None
     with open(os.path.join(os.path.dirname(os.path.abspath(A.__file__)), "csrc", "gemm.hip"), "rb") as f:
         if args.workload == "C2" and hashlib.sha256(f.read()).hexdigest() == COUNTED_GEMM_SHA256:
             traffic = COUNTED_GATE_UP_BYTES
-
     out = {
-        "metric": "scored step-tokens/sec on 1 MI355X", "value": T / (ms_per_step * 1e-3), "unit": "scored step-tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "scored step-tokens/sec on 1 MI355X", "value": head["step_tokens_per_s"], "unit": "scored step-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "layers": L, "d_model": w.model.d_model, "batch": batch.batch,
-                   "prefix_tokens": int(batch.prefix_lens.sum()), "step_tokens": T, "kv": f"paged-16 {w.tables}"},
-        "roofline": {"bound": "mfma", "kernel": gu_kernel, "achieved": achieved,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
-                     "avg_launch_ms": gu_avg_ms, "launches": n, "flops_per_launch": gu_flops},
+        "config": {"workload": head["workload"], "layers": head["layers"], "d_model": head["d_model"], "batch": head["batch"],
+                   "prefix_tokens": head["prefix_tokens"], "step_tokens": head["step_tokens"], "kv": head["kv"]},
+        "roofline": {"bound": "mfma", "kernel": dom["kernel"], "achieved": dom["TFLOPs"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom["mfma_frac"], "traffic": traffic,
+                     "avg_launch_ms": dom["avg_launch_ms"], "launches": dom["launches"],
+                     "flops_per_launch": dom["flops_per_launch"]},
+        "attention_hbm_frac": {e["workload"].split("-")[0]: round(e["attention"]["hbm_frac"], 4) for e in per_config},
+        "gemm_mfma_frac": {e["workload"].split("-")[0]: round(e["gemm"]["aggregate_mfma_frac"], 4) for e in per_config},
+        "per_config": per_config,
     }
-
-    if args.breakdown:
-        stages = {"qkv": A.ARB_STAGE_QKV, "attention": A.ARB_STAGE_ATTENTION, "oproj": A.ARB_STAGE_OPROJ,
-                  "gate_up": A.ARB_STAGE_GATE_UP, "down": A.ARB_STAGE_DOWN, "norm": A.ARB_STAGE_NORM,
-                  "rope_append": A.ARB_STAGE_ROPE_APPEND}
-        bd = {}
-        for name, sid in stages.items():
-            t = A.StageTimer(model, sid, 3 * L)
-            t.arm()
-            for _ in range(3):
-                step()
-            torch.cuda.synchronize()
-            d = t.durations_ms(t.disarm())
-            t.close()
-            bd[name] = sum(d) / 3
-        m = w.model
-        kv_bytes = float(((batch.prefix_lens + batch.step_lens) * 2 * m.n_kv_heads * m.head_dim * 2).sum())
-        attn_flops = float(4 * m.n_q_heads * m.head_dim * (batch.step_lens * batch.prefix_lens + batch.step_lens * (batch.step_lens + 1) / 2).sum())
-        qo_bytes = 2.0 * T * m.n_q_heads * m.head_dim * 2
-        out["stage_ms_per_step"] = bd
-        out["attention"] = {"ms_per_layer": bd["attention"] / L, "GBps": (kv_bytes + qo_bytes) / (bd["attention"] / L * 1e-3) / 1e9,
-                            "hbm_frac": (kv_bytes + qo_bytes) / (bd["attention"] / L * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                            "TFLOPs": attn_flops / (bd["attention"] / L * 1e-3) / 1e12}
-        gemm_flops = {"qkv": 2.0 * T * m.qkv_rows * m.d_model, "oproj": 2.0 * T * m.d_model * m.n_q_heads * m.head_dim,
-                      "gate_up": 2.0 * T * 2 * m.d_ffn * m.d_model, "down": 2.0 * T * m.d_model * m.d_ffn}
-        out["gemm_TFLOPs"] = {k: v / (bd[k] / L * 1e-3) / 1e12 for k, v in gemm_flops.items()}
-
-    if args.cpu_layers < 0:
-        args.cpu_layers = L
-    if args.cpu_layers > 0:
-        out["cpu_baseline"] = cpu_baseline(w, sess, min(args.cpu_layers, L))
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
     print(json.dumps(out))
 
 
