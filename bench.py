@@ -100,7 +100,7 @@ def cpu_baseline(name, w, sess, layers: int):
 STAGES = ("qkv", "attention", "oproj", "gate_up", "down", "norm", "rope_append")
 
 
-def run_config(name, steps, warmup, cpu_layers, copy_probe_mib=0):
+def run_config(name, steps, warmup, cpu_layers, copy_probe_mib=0, stage_reps=3):
     """Sets one workload up on the device, times `steps` calls after `warmup`, then (outside the timed
     region) times every stage with the library's event hook and runs the CPU sample."""
     import torch
@@ -158,8 +158,8 @@ def run_config(name, steps, warmup, cpu_layers, copy_probe_mib=0):
     ids = {"qkv": A.ARB_STAGE_QKV, "attention": A.ARB_STAGE_ATTENTION, "oproj": A.ARB_STAGE_OPROJ,
            "gate_up": A.ARB_STAGE_GATE_UP, "down": A.ARB_STAGE_DOWN, "norm": A.ARB_STAGE_NORM,
            "rope_append": A.ARB_STAGE_ROPE_APPEND}
-    reps, stage_ms = 3, {}
-    for sname in STAGES:
+    reps, stage_ms = max(stage_reps, 1), {}
+    for sname in STAGES if stage_reps > 0 else ():
         t = A.StageTimer(model, ids[sname], reps * L)
         t.arm()
         for _ in range(reps):
@@ -168,6 +168,14 @@ def run_config(name, steps, warmup, cpu_layers, copy_probe_mib=0):
         dur = t.durations_ms(t.disarm())
         t.close()
         stage_ms[sname] = sum(dur) / reps
+    if stage_reps <= 0:        # counter runs: the timed steps only
+        model.close()
+        return {"workload": w.name, "layers": L, "d_model": d, "batch": batch.batch, "step_tokens": T,
+                "prefix_tokens": int(batch.prefix_lens.sum()), "kv": f"paged-16 {w.tables}", "ms_per_step": ms_per_step,
+                "step_tokens_per_s": T / (ms_per_step * 1e-3),
+                "gemm": {"dominant_kernel": {"kernel": gu_kernel, "avg_launch_ms": gu_avg_ms, "launches": n,
+                                             "flops_per_launch": gu_flops, "TFLOPs": gu_achieved,
+                                             "mfma_frac": gu_achieved / PEAK_BF16_TFLOPS}}}
     # algorithmic work of one layer
     ctx = (batch.prefix_lens + batch.step_lens).astype(float)
     s, p = batch.step_lens.astype(float), batch.prefix_lens.astype(float)
@@ -222,6 +230,8 @@ def main():
     ap.add_argument("--configs", default="C2,C3,C4,C5", help="workloads reported in per_config (comma separated; '' = only the headline)")
     ap.add_argument("--cpu-layers", type=int, default=-1, help="layers of the oracle sample (-1 = all, 0 = skip the CPU baseline)")
     ap.add_argument("--breakdown", action="store_true", help="kept for compatibility: stage times are always reported")
+    ap.add_argument("--stage-reps", type=int, default=3, help="extra passes per stage for the per-stage times (0: none, "
+                    "for hardware-counter runs; per_config then holds the step times only)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the warm-up, run one plain device copy of this many MiB (a kernel of known traffic "
                          "that hardware-counter runs are scaled by)")
@@ -240,7 +250,7 @@ def main():
     per_config = []
     for i, name in enumerate(names):
         per_config.append(run_config(name, args.steps, args.warmup, args.cpu_layers,
-                                     args.copy_probe_mib if i == 0 else 0))
+                                     args.copy_probe_mib if i == 0 else 0, args.stage_reps))
         print(f"bench: {name} done: {per_config[-1]['ms_per_step']:.3f} ms per step", file=sys.stderr, flush=True)
     per_config.sort(key=lambda e: e["workload"])
     head = next(e for e in per_config if e["workload"].startswith(args.workload))
@@ -261,10 +271,11 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom["mfma_frac"], "traffic": traffic,
                      "avg_launch_ms": dom["avg_launch_ms"], "launches": dom["launches"],
                      "flops_per_launch": dom["flops_per_launch"]},
-        "attention_hbm_frac": {e["workload"].split("-")[0]: round(e["attention"]["hbm_frac"], 4) for e in per_config},
-        "gemm_mfma_frac": {e["workload"].split("-")[0]: round(e["gemm"]["aggregate_mfma_frac"], 4) for e in per_config},
         "per_config": per_config,
     }
+    if args.stage_reps > 0:
+        out["attention_hbm_frac"] = {e["workload"].split("-")[0]: round(e["attention"]["hbm_frac"], 4) for e in per_config}
+        out["gemm_mfma_frac"] = {e["workload"].split("-")[0]: round(e["gemm"]["aggregate_mfma_frac"], 4) for e in per_config}
     if "cpu_baseline" in head:
         out["cpu_baseline"] = head["cpu_baseline"]
     print(json.dumps(out))

@@ -273,10 +273,13 @@ arb_status arb_stage_gemm_w4(const void *A, const void *packed, const void *scal
 int32_t arb_gemm_large_tile_columns(int32_t M, int32_t N, int32_t K, int32_t epilogue);
 
 /* Append-attention of one layer.  q: device bf16, row t at q + t*q_row_stride elements, heads contiguous
- * [Hq, hd], already rotated; the pools already hold the step's keys/values.  out: bf16 [T, Hq*hd]. */
-arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, const void *k_pool,
-                               const void *v_pool, const arb_batch *batch, void *out, void *ws, size_t ws_bytes,
-                               void *stream);
+ * [Hq, hd], already rotated; the pools already hold the step's keys/values.  out: bf16 [T, Hq*hd].
+ * q_scaled == 0: q is the rotated query itself and the logits are q.k / sqrt(hd).  q_scaled != 0: q already
+ * carries the factor log2(e) / sqrt(hd), as the forward's rotary stage stores it (multiplied in fp32 before
+ * the one rounding to bf16), and q.k is taken as the logit in log2 units: the kernel of the forward. */
+arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, int32_t q_scaled,
+                               const void *k_pool, const void *v_pool, const arb_batch *batch, void *out, void *ws,
+                               size_t ws_bytes, void *stream);
 
 /* RMSNorm rows: x fp32 [T, d] -> out bf16 [T, d] = x / sqrt(mean(x^2) + eps) * g. */
 arb_status arb_stage_rmsnorm(const float *x, const float *g, float eps, int32_t T, int32_t d, void *out, void *stream);

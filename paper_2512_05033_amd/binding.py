@@ -102,8 +102,8 @@ def load_library(path: Optional[str] = None):
     lib.arb_pack_k_blocked.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_gemm_w4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                       C.c_int32, C.c_void_p]
-    lib.arb_stage_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(_Batch),
-                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.arb_stage_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.POINTER(_Batch), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.arb_stage_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_rope_append.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_Batch),
                                           C.c_void_p, C.c_size_t, C.c_void_p]
@@ -433,13 +433,15 @@ def arb_gemm_large_tile_columns(M: int, N: int, K: int, epilogue: int) -> int:
 
 
 def arb_stage_attention(model: Model, q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
-                        batch: DeviceBatch, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """q bf16 [T, row] whose first Hq*hd columns are the (rotated) query heads -> bf16 [T, Hq*hd]."""
+                        batch: DeviceBatch, ws: Optional[torch.Tensor] = None, stream=None,
+                        q_scaled: bool = False) -> torch.Tensor:
+    """q bf16 [T, row] whose first Hq*hd columns are the (rotated) query heads -> bf16 [T, Hq*hd].
+    q_scaled: q already carries the factor log2(e)/sqrt(head_dim)."""
     _dev(q, torch.bfloat16), _dev(k_pool, torch.bfloat16), _dev(v_pool, torch.bfloat16)
     out = torch.empty(batch.total_tokens, model.cfg.n_q_heads * model.cfg.head_dim, dtype=torch.bfloat16,
                       device=q.device)
     ws = _workspace(model, batch, ws)
-    _check(load_library().arb_stage_attention(model.handle, _ptr(q), q.shape[1], _ptr(k_pool), _ptr(v_pool),
+    _check(load_library().arb_stage_attention(model.handle, _ptr(q), q.shape[1], int(q_scaled), _ptr(k_pool), _ptr(v_pool),
                                               C.byref(batch.c), _ptr(out), ws.data_ptr(), ws.numel(), _stream(stream)))
     return out
 

@@ -332,15 +332,16 @@ static arb_status forward(arb_model *m, const arb_kv *kv, const arb_batch *bt, b
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_ROPE_APPEND, st);
+      // the queries leave the rotary kernel multiplied by log2(e)/sqrt(hd) (in fp32, before their one rounding)
       s = launch_rope_append(w.qkv, w.parts, sq > 1 ? sq : 0, w.cs, w.tok_slot, (bf16 *)kv->k_pool[l], (bf16 *)kv->v_pool[l], T, c.n_q_heads,
-                             c.n_kv_heads, c.head_dim, st);
+                             c.n_kv_heads, c.head_dim, attention_q_scale(c.head_dim), st);
     }
     if (s) return s;
     {
       TraceScope t(m, ARB_STAGE_ATTENTION, st);
       s = launch_attention(w.qkv, m->qkv_rows(), (const bf16 *)kv->k_pool[l], (const bf16 *)kv->v_pool[l],
                            bt->block_tables, bt->max_blocks_per_seq, bt->prefix_lens, bt->cu_step_lens, B, T,
-                           c.n_q_heads, c.n_kv_heads, c.head_dim, plan, w.tok_pos, w.attn, w.attn_ws, w.attn_ws_bytes, st);
+                           c.n_q_heads, c.n_kv_heads, c.head_dim, plan, w.tok_pos, w.attn, w.attn_ws, w.attn_ws_bytes, st, true);
     }
     if (s) return s;
     {
@@ -541,9 +542,9 @@ extern "C" int32_t arb_gemm_large_tile_columns(int32_t M, int32_t N, int32_t K, 
   return gemm_large_cols(M, N, K, epilogue, 1);
 }
 
-extern "C" arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, const void *k_pool,
-                                          const void *v_pool, const arb_batch *batch, void *out, void *ws,
-                                          size_t ws_bytes, void *stream) {
+extern "C" arb_status arb_stage_attention(const arb_model *m, const void *q, int32_t q_row_stride, int32_t q_scaled,
+                                          const void *k_pool, const void *v_pool, const arb_batch *batch, void *out,
+                                          void *ws, size_t ws_bytes, void *stream) {
   if (!m) return arb_fail(ARB_EINVAL, "null model");
   const arb_model_cfg &c = m->cfg;
   BatchInfo info;
@@ -557,7 +558,7 @@ extern "C" arb_status arb_stage_attention(const arb_model *m, const void *q, int
   return launch_attention((const bf16 *)q, q_row_stride, (const bf16 *)k_pool, (const bf16 *)v_pool,
                           batch->block_tables, batch->max_blocks_per_seq, batch->prefix_lens, batch->cu_step_lens,
                           batch->batch, batch->total_tokens, c.n_q_heads, c.n_kv_heads, c.head_dim, plan, nullptr, (bf16 *)out,
-                          ws, ws_bytes, (hipStream_t)stream);
+                          ws, ws_bytes, (hipStream_t)stream, q_scaled != 0);
 }
 
 extern "C" arb_status arb_stage_rmsnorm(const float *x, const float *g, float eps, int32_t T, int32_t d, void *out,
@@ -589,7 +590,7 @@ extern "C" arb_status arb_stage_rope_append(const arb_model *m, void *qkv, void 
     return s;
   if ((s = launch_rope_table(tok_pos, (int)T, c.head_dim, c.rope_base, cs, st))) return s;
   return launch_rope_append((bf16 *)qkv, nullptr, 0, cs, tok_slot, (bf16 *)k_pool, (bf16 *)v_pool, (int)T, c.n_q_heads,
-                            c.n_kv_heads, c.head_dim, st);
+                            c.n_kv_heads, c.head_dim, 1.0f, st);
 }
 
 extern "C" arb_status arb_stage_layers(arb_model *m, const arb_kv *kv, const arb_batch *batch, int32_t layer_begin,

@@ -58,16 +58,26 @@ template <int HD>
 __device__ __forceinline__ int v_off(int key, int chunk) { return key * HD + ((chunk ^ v_swizzle<HD>(key)) << 3); }
 
 // One 64-key tile for one wave: scores, online softmax update, O^T accumulation.
-template <int HD>
+//
+// PRESCALED: the queries arrive multiplied by log2(e)/sqrt(hd) (the forward's rotary kernel stores them that
+// way, in fp32 before their one rounding), so K Q^T is already the logit in log2 units, and the score MFMAs
+// start from the accumulator tuple `negm` (every element = minus the lane's reference maximum): the matrix
+// pipe delivers s - m, and the vector ALU, which is the busier pipe of this kernel, is left with one exp2,
+// half a max3, half a dot2 (row sum over the rounded probabilities, the ones the PV product uses) and half a
+// convert per score.  Otherwise (queries as given, exact) the scale and the reference are applied to the fp32
+// scores by one FMA per score; negm[0] then holds minus the reference.
+template <int HD, bool PRESCALED>
 __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, const bf16x8 (&qf)[HD / 16], f32x16 (&o)[HD / 32],
-                                            float &m_run, float &l_run, int ts, int limit, float scale_log2, int col,
-                                            int half, int lane) {
+                                            f32x16 &negm, float &m_run, float &l_run, int ts, int limit, float scale_log2,
+                                            int col, int half, int lane) {
   constexpr int KSTEPS = HD / 16, MT = HD / 32;
   f32x16 st[2];
+  if (!PRESCALED) {
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
+      for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
+  }
   {
     // K fragments of step kk+1 are read while the MFMAs of step kk run
     bf16x8 kf[2][2];
@@ -81,7 +91,8 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
           kf[(kk + 1) & 1][t] = *(const bf16x8 *)&sk[k_off<HD>(t * 32 + col, (kk + 1) * 2 + half)];
       }
 #pragma unroll
-      for (int t = 0; t < 2; ++t) st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][t], qf[kk], st[t], 0, 0, 0);
+      for (int t = 0; t < 2; ++t)
+        st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][t], qf[kk], PRESCALED && kk == 0 ? negm : st[t], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -94,39 +105,72 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
 #pragma unroll
       for (int r = 0; r < 16; ++r) st[t][r] = (t * 32 + 8 * (r >> 2) + (r & 3)) <= vis ? st[t][r] : -INFINITY;
   }
-  // running max over the raw logits (the positive scale commutes with max)
+  // largest logit of the tile (the positive scale commutes with max), then relative to the reference maximum
   float mx = -INFINITY;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[t][r]);
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  if (!PRESCALED) mx = fmaf(mx, scale_log2, negm[0]);
   // The reference maximum m_run is advanced only when some row's maximum has outgrown it by more
   // than kLazyLog2: until then exp2(s - m_run) <= 2^kLazyLog2, far inside the range of bf16 and
   // fp32, and o / l is unchanged because both carry the same factor.  Most tiles then skip the
-  // rescaling of the accumulators.
-  const float m_new = fmaxf(m_run, mx * scale_log2);
-  if (__builtin_amdgcn_ballot_w64(m_new > m_run + kLazyLog2) != 0) {     // also the first visible key (m_run = -inf)
-    const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));   // m_run = -inf -> 0
+  // rescaling of the accumulators.  A row without a visible key so far has m_run = -inf and the
+  // reference 0; its first visible key always sets the reference.
+  if (__builtin_amdgcn_ballot_w64(mx > kLazyLog2 || (m_run == -INFINITY && mx > -INFINITY)) != 0) {
+    const float m_use = m_run == -INFINITY ? 0.f : m_run;
+    const float m_new = fmaxf(m_run, m_use + mx);                    // -inf only while nothing is visible
+    const float m_new_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new_use);   // m_run = -inf -> 0
     l_run *= alpha;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[mt][r] *= alpha;
+    if (PRESCALED) {
+      const float shift = m_new_use - m_use;                         // the scores were taken against the old reference
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[t][r] -= shift;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) negm[r] = -m_new_use;
+    } else {
+      negm[0] = -m_new_use;
+    }
     m_run = m_new;
   }
-  const float m_use = m_run == -INFINITY ? 0.f : m_run;
-  float l_add = 0.f;
+  if (!PRESCALED) {
+    const float nm = negm[0];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st[t][r] = fmaf(st[t][r], scale_log2, nm);
+  }
   bf16x8 pf[2][2];
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float pv = __builtin_amdgcn_exp2f(fmaf(st[t][r], scale_log2, -m_use));   // raw v_exp_f32; -inf -> 0
-      l_add += pv;
-      pf[t][r >> 3][r & 7] = (bf16)pv;
-    }
-  l_run += l_add;
+    for (int r = 0; r < 16; ++r) pf[t][r >> 3][r & 7] = (bf16)__builtin_amdgcn_exp2f(st[t][r]);   // raw v_exp_f32; -inf -> 0
+  // row sum over the probabilities as the PV product sees them (bf16), two per instruction
+  {
+    bf16x2 ones;
+    ones[0] = ones[1] = (bf16)1.0f;
+    float l_add = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          bf16x2 pr;
+          pr[0] = pf[t][u][e];
+          pr[1] = pf[t][u][e + 1];
+          l_add = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_add, false);
+        }
+    l_run += l_add;
+  }
   // O^T += V^T P^T; V^T fragments by transpose reads (see the header comment)
   const int j16 = lane & 15;
   const int vcol = 16 * ((lane >> 4) & 1) + 4 * (j16 & 3);     // within a 32-column tile
@@ -150,7 +194,7 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
     }
 }
 
-template <int HD, bool SPLIT>
+template <int HD, bool SPLIT, bool PRESCALED>
 __global__ __launch_bounds__(256, 2) void attention_kernel(
     const bf16 *__restrict__ q, int q_row_stride, const bf16 *__restrict__ k_pool, const bf16 *__restrict__ v_pool,
     const int32_t *__restrict__ block_tables, int max_blocks, const int32_t *__restrict__ prefix_lens,
@@ -221,6 +265,9 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[mt][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  f32x16 negm;                               // minus the reference maximum (PRESCALED: in every element, the score MFMAs' C operand)
+#pragma unroll
+  for (int r = 0; r < 16; ++r) negm[r] = 0.f;
 
   // Tile loads.  One wave-wide direct-to-LDS load moves KPL whole keys (1 KB) of one 16-key block:
   // the block id is wave-uniform (scalar), lane l lands in chunk slot l % CPK of key l / CPK and
@@ -276,13 +323,13 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(
     dma(K1, V1, min(t + 1, last_tile));
     lookup(min(t + 2, last_tile));
     __builtin_amdgcn_sched_barrier(0);
-    if (wave_active) attend_tile<HD>(K0, V0, qf, o, m_run, l_run, kv_begin + t * KT, limit, scale_log2, col, half, lane);
+    if (wave_active) attend_tile<HD, PRESCALED>(K0, V0, qf, o, negm, m_run, l_run, kv_begin + t * KT, limit, scale_log2, col, half, lane);
     __syncthreads();
     if (t + 1 < n_tiles) {
       dma(K0, V0, min(t + 2, last_tile));
       lookup(min(t + 3, last_tile));
       __builtin_amdgcn_sched_barrier(0);
-      if (wave_active) attend_tile<HD>(K1, V1, qf, o, m_run, l_run, kv_begin + (t + 1) * KT, limit, scale_log2, col, half, lane);
+      if (wave_active) attend_tile<HD, PRESCALED>(K1, V1, qf, o, negm, m_run, l_run, kv_begin + (t + 1) * KT, limit, scale_log2, col, half, lane);
       __syncthreads();
     }
   }
@@ -388,6 +435,8 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const bf16 *__rest
 static const int kTargetWorkgroups = 512;    // two resident workgroups per CU on 256 CUs
 static const int kMinChunk = 256, kMaxChunk = 4096, kMaxChunkDecode = 8192, kMaxSplits = 64;
 
+float attention_q_scale(int head_dim) { return (float)(1.4426950408889634 / sqrt((double)head_dim)); }
+
 int attention_splits_cap(int max_ctx) {
   if (max_ctx <= 0) return 1;
   const int n = ceil_div(max_ctx, kMinChunk);
@@ -431,7 +480,7 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
                             const int32_t *block_tables, int max_blocks_per_seq, const int32_t *prefix_lens,
                             const int32_t *cu_step_lens, int batch, int total_tokens, int n_q_heads, int n_kv_heads,
                             int head_dim, const AttnPlan &plan, const int32_t *tok_pos_in, bf16 *out, void *ws, size_t ws_bytes,
-                            hipStream_t st) {
+                            hipStream_t st, bool q_prescaled) {
   if (batch == 0 || total_tokens == 0) return ARB_OK;
   if (head_dim != 64 && head_dim != 128) return arb_fail(ARB_EUNSUPPORTED, "attention: head_dim %d", head_dim);
   const bool split = plan.max_splits > 1;
@@ -453,15 +502,18 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
         return s;
     }
   }
-  const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)head_dim));
+  const float scale_log2 = attention_q_scale(head_dim);
   const int n_groups = batch * n_kv_heads * plan.max_splits;      // (sequence, split, kv head)
   const dim3 grid(ceil_div(n_groups, 8) * 8 * plan.max_qtiles), block(256);
-#define ARB_ATTN_LAUNCH(HD, SPLIT)                                                                                 \
-  hipLaunchKernelGGL((attention_kernel<HD, SPLIT>), grid, block, 0, st, q, q_row_stride, k_pool, v_pool,           \
+#define ARB_ATTN_LAUNCH(HD, SPLIT, PRE)                                                                            \
+  hipLaunchKernelGGL((attention_kernel<HD, SPLIT, PRE>), grid, block, 0, st, q, q_row_stride, k_pool, v_pool,      \
                      block_tables, max_blocks_per_seq, prefix_lens, cu_step_lens, total_tokens, n_q_heads,         \
                      n_kv_heads, plan.max_qtiles, plan.max_splits, plan.kv_chunk, scale_log2, out, part_acc, part_ml, n_groups)
-  if (head_dim == 128) { if (split) ARB_ATTN_LAUNCH(128, true); else ARB_ATTN_LAUNCH(128, false); }
-  else                 { if (split) ARB_ATTN_LAUNCH(64, true);  else ARB_ATTN_LAUNCH(64, false); }
+#define ARB_ATTN_PICK(HD)                                                                                          \
+  if (split) { if (q_prescaled) ARB_ATTN_LAUNCH(HD, true, true); else ARB_ATTN_LAUNCH(HD, true, false); }          \
+  else       { if (q_prescaled) ARB_ATTN_LAUNCH(HD, false, true); else ARB_ATTN_LAUNCH(HD, false, false); }
+  if (head_dim == 128) { ARB_ATTN_PICK(128) } else { ARB_ATTN_PICK(64) }
+#undef ARB_ATTN_PICK
 #undef ARB_ATTN_LAUNCH
   ARB_CHECK_LAUNCH("attention");
   if (split) {

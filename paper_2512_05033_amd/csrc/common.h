@@ -93,7 +93,10 @@ arb_status launch_attention(const bf16 *q, int q_row_stride, const bf16 *k_pool,
                             const int32_t *block_tables, int max_blocks_per_seq, const int32_t *prefix_lens,
                             const int32_t *cu_step_lens, int batch, int total_tokens, int n_q_heads, int n_kv_heads,
                             int head_dim, const AttnPlan &plan, const int32_t *tok_pos_in, bf16 *out, void *ws, size_t ws_bytes,
-                            hipStream_t st);
+                            hipStream_t st, bool q_prescaled);
+// log2(e) / sqrt(head_dim): the factor the attention kernel wants folded into the queries (q_prescaled), so that
+// its score products are logits in log2 units; launch_rope_append applies it (q_scale) before it rounds q.
+float attention_q_scale(int head_dim);
 
 // elementwise.hip
 arb_status launch_token_meta(const int32_t *prefix_lens, const int32_t *cu_step_lens, const int32_t *block_tables,
@@ -114,7 +117,7 @@ arb_status launch_rmsnorm(float *h, const float *parts, int n_parts, const float
 // [n_parts, T, (Hq+2Hkv)*hd] instead of from qkv; the rotated q is written to qkv (bf16) either way.
 arb_status launch_rope_append(bf16 *qkv, const float *parts, int n_parts, const f32x2 *cs, const int32_t *tok_slot,
                               bf16 *k_pool, bf16 *v_pool, int T, int n_q_heads, int n_kv_heads, int head_dim,
-                              hipStream_t st);
+                              float q_scale, hipStream_t st);
 arb_status launch_final_norm_head(const float *h, const float *parts, int n_parts, const float *g, float eps, int T,
                                   int d, const float *w_head, const float *w_head1, bf16 *hidden_out, float *tok_dot,
                                   hipStream_t st);     // w_head1: class-1 row of a two-class head, else null

@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv
                                                           const f32x2 *__restrict__ cs,
                                                           const int32_t *__restrict__ tok_slot,
                                                           bf16 *__restrict__ k_pool, bf16 *__restrict__ v_pool,
-                                                          int Hq, int Hkv, int hd) {
+                                                          int Hq, int Hkv, int hd, float q_scale) {
   const int j = blockIdx.x;
   const int half = hd / 2, units_per_head = half / 2, n_heads = Hq + 2 * Hkv;
   bf16 *row = qkv + (size_t)j * n_heads * hd;
@@ -323,10 +323,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv
     bf16x2 oa, ob;
     if (head < Hq + Hkv) {
       const f32x2 cs0 = cs[(size_t)j * half + t], cs1 = cs[(size_t)j * half + t + 1];
-      oa[0] = (bf16)(a[0] * cs0[0] - b[0] * cs0[1]);
-      ob[0] = (bf16)(b[0] * cs0[0] + a[0] * cs0[1]);
-      oa[1] = (bf16)(a[1] * cs1[0] - b[1] * cs1[1]);
-      ob[1] = (bf16)(b[1] * cs1[0] + a[1] * cs1[1]);
+      const float f = head < Hq ? q_scale : 1.0f;          // queries may carry a constant factor for the attention kernel
+      oa[0] = (bf16)((a[0] * cs0[0] - b[0] * cs0[1]) * f);
+      ob[0] = (bf16)((b[0] * cs0[0] + a[0] * cs0[1]) * f);
+      oa[1] = (bf16)((a[1] * cs1[0] - b[1] * cs1[1]) * f);
+      ob[1] = (bf16)((b[1] * cs1[0] + a[1] * cs1[1]) * f);
     } else {
       oa[0] = (bf16)a[0]; oa[1] = (bf16)a[1]; ob[0] = (bf16)b[0]; ob[1] = (bf16)b[1];
     }
@@ -345,16 +346,16 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16 *__restrict__ qkv
 
 arb_status launch_rope_append(bf16 *qkv, const float *parts, int n_parts, const f32x2 *cs, const int32_t *tok_slot,
                               bf16 *k_pool, bf16 *v_pool, int T, int n_q_heads, int n_kv_heads, int head_dim,
-                              hipStream_t st) {
+                              float q_scale, hipStream_t st) {
   if (T == 0) return ARB_OK;
   const size_t stride = (size_t)T * (n_q_heads + 2 * n_kv_heads) * head_dim;
   const dim3 grid(T, ceil_div((n_q_heads + 2 * n_kv_heads) * (head_dim / 4), 256));
   if (n_parts > 0)
     hipLaunchKernelGGL((rope_append_kernel<true>), grid, dim3(256), 0, st, qkv, parts, n_parts, stride, cs, tok_slot,
-                       k_pool, v_pool, n_q_heads, n_kv_heads, head_dim);
+                       k_pool, v_pool, n_q_heads, n_kv_heads, head_dim, q_scale);
   else
     hipLaunchKernelGGL((rope_append_kernel<false>), grid, dim3(256), 0, st, qkv, (const float *)nullptr, 0, stride, cs,
-                       tok_slot, k_pool, v_pool, n_q_heads, n_kv_heads, head_dim);
+                       tok_slot, k_pool, v_pool, n_q_heads, n_kv_heads, head_dim, q_scale);
   ARB_CHECK_LAUNCH("rope_append");
   return ARB_OK;
 }

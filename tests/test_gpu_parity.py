@@ -289,7 +289,7 @@ def test_first_stop_bit_exact(A):
 
 # ---------------------------------------------------------------------- attention
 
-def _attention_case(A, shape, prefix, steps, peaky, seed):
+def _attention_case(A, shape, prefix, steps, peaky, seed, q_scaled=False):
     m, model = _stage_model(A, shape, seed)
     wl, batch = _ragged_batch(m, prefix, steps, seed)
     db = H().device_batch(batch)
@@ -304,8 +304,13 @@ def _attention_case(A, shape, prefix, steps, peaky, seed):
             for pos in {0, p // 2, p + s - 1}:
                 blk, off = batch.block_tables[b][pos // 16], pos % 16
                 ks[0][blk, :, off, :] = qf[batch.cu_step_lens[b + 1] - 1, 0, :] * 0.5
-    got = A.arb_stage_attention(model, q, ks[0], vs[0], db)
-    ref = O.append_attention(bf16_np(q).reshape(T, -1, m.head_dim)[:, :m.n_q_heads], W.bf16_bits(ks[0]),
+    got = A.arb_stage_attention(model, q, ks[0], vs[0], db, q_scaled=q_scaled)
+    qf = bf16_np(q)
+    if q_scaled:
+        # the kernel takes q.k as the logit in log2 units; the same logits by the definition q'.k / sqrt(hd)
+        # belong to q' = q ln(2) sqrt(hd) (exact in fp64 up to its own rounding)
+        qf = qf * (np.log(2.0) * np.sqrt(float(m.head_dim)))
+    ref = O.append_attention(qf.reshape(T, -1, m.head_dim)[:, :m.n_q_heads], W.bf16_bits(ks[0]),
                              W.bf16_bits(vs[0]), batch.prefix_lens, batch.cu_step_lens, batch.block_tables, 16)
     return bf16_np(got).reshape(T, m.n_q_heads, m.head_dim), ref
 
@@ -321,8 +326,9 @@ def _attention_case(A, shape, prefix, steps, peaky, seed):
     (W.TARGET_8B, [0, 60, 130, 250, 2000], [33, 64, 64, 240, 129]),      # G=4: 132, 256, 256, 960, 516 rows
     (W.ROUTER_1P5B, [10, 5000, 333], [40, 150, 64]),                     # G=6: 240, 900 rows; 384 rows (128-row kernel)
 ])
-def test_attention_stage(A, shape, prefix, steps, peaky):
-    got, ref = _attention_case(A, shape, prefix, steps, peaky, 31)
+@pytest.mark.parametrize("q_scaled", [False, True])
+def test_attention_stage(A, shape, prefix, steps, peaky, q_scaled):
+    got, ref = _attention_case(A, shape, prefix, steps, peaky, 31, q_scaled)
     assert rel_err(got, ref) < 1e-2
     # row-wise as well, so a wrong small row cannot hide behind a large one
     row_err = np.abs(got - ref).max(axis=-1) / (np.abs(ref).max(axis=-1) + 1e-3)
@@ -338,7 +344,7 @@ def test_attention_stage_random_ragged_batches(A, seed):
     n = int(rng.integers(1, 10))
     prefix = [int(v) for v in rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 300, 700, 1500, 2600], size=n)]
     steps = [int(v) for v in rng.choice([1, 2, 5, 16, 21, 22, 33, 43, 64, 70], size=n)]
-    got, ref = _attention_case(A, shape, prefix, steps, False, 50 + seed)
+    got, ref = _attention_case(A, shape, prefix, steps, False, 50 + seed, q_scaled=seed % 2 == 0)
     assert rel_err(got, ref) < 1e-2
     row_err = np.abs(got - ref).max(axis=-1) / (np.abs(ref).max(axis=-1) + 1e-3)
     assert row_err.max() < 3e-2
