@@ -79,20 +79,23 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
       for (int r = 0; r < 16; ++r) st[t][r] = 0.f;
   }
   {
-    // K fragments of step kk+1 are read while the MFMAs of step kk run
-    bf16x8 kf[2][2];
+    // K fragments are requested two steps ahead of the MFMAs that take them (an LDS read takes longer
+    // than the two MFMAs of a step)
+    bf16x8 kf[3][2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) kf[0][t] = *(const bf16x8 *)&sk[k_off<HD>(t * 32 + col, half)];
+    for (int pre = 0; pre < 2; ++pre)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) kf[pre][t] = *(const bf16x8 *)&sk[k_off<HD>(t * 32 + col, pre * 2 + half)];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
-      if (kk + 1 < KSTEPS) {
+      if (kk + 2 < KSTEPS) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
-          kf[(kk + 1) & 1][t] = *(const bf16x8 *)&sk[k_off<HD>(t * 32 + col, (kk + 1) * 2 + half)];
+          kf[(kk + 2) % 3][t] = *(const bf16x8 *)&sk[k_off<HD>(t * 32 + col, (kk + 2) * 2 + half)];
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t)
-        st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk & 1][t], qf[kk], PRESCALED && kk == 0 ? negm : st[t], 0, 0, 0);
+        st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk % 3][t], qf[kk], PRESCALED && kk == 0 ? negm : st[t], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -105,13 +108,14 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
 #pragma unroll
       for (int r = 0; r < 16; ++r) st[t][r] = (t * 32 + 8 * (r >> 2) + (r & 3)) <= vis ? st[t][r] : -INFINITY;
   }
-  // largest logit of the tile (the positive scale commutes with max), then relative to the reference maximum
+  // largest logit this lane holds for its query (the positive scale commutes with max), relative to the
+  // reference maximum.  A query's keys are split between lanes l and l ^ 32; the two are only combined
+  // (a cross-lane exchange) on the rare path below.
   float mx = -INFINITY;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[t][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
   if (!PRESCALED) mx = fmaf(mx, scale_log2, negm[0]);
   // The reference maximum m_run is advanced only when some row's maximum has outgrown it by more
   // than kLazyLog2: until then exp2(s - m_run) <= 2^kLazyLog2, far inside the range of bf16 and
@@ -119,6 +123,7 @@ __device__ __forceinline__ void attend_tile(const bf16 *sk, const bf16 *sv, cons
   // rescaling of the accumulators.  A row without a visible key so far has m_run = -inf and the
   // reference 0; its first visible key always sets the reference.
   if (__builtin_amdgcn_ballot_w64(mx > kLazyLog2 || (m_run == -INFINITY && mx > -INFINITY)) != 0) {
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_use = m_run == -INFINITY ? 0.f : m_run;
     const float m_new = fmaxf(m_run, m_use + mx);                    // -inf only while nothing is visible
     const float m_new_use = m_new == -INFINITY ? 0.f : m_new;
