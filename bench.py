@@ -221,6 +221,69 @@ def run_config(name, steps, warmup, cpu_layers, copy_probe_mib=0, stage_reps=3):
     return entry
 
 
+def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4):
+    """Algorithm 1 end to end on three synthetic roles (draft: 1.5B shape, target: 8B shape, router: 1.5B shape with
+    the linear head; random-init weights, a common vocabulary): reasoning steps per second of the whole loop
+    (draft step token by token, router score, target step for the escalated sequences).  The separator is a
+    token the random draft really emits and the threshold the median of a probe pass's scores, so steps end
+    early for some sequences and both branches of the rule are taken."""
+    from dataclasses import replace
+
+    import numpy as np
+    import torch
+
+    import harness
+    import paper_2512_05033_amd as A
+    import workloads as W
+    from paper_2512_05033_amd.arbitrage import Arbitrage, Role
+
+    vocab = min(W.C2.model.vocab, W.C3.model.vocab)
+    blocks_per_seq = (prompt + (alg_steps + 1) * max_step_tokens + 15) // 16 + 1
+    n_blocks = n_questions * blocks_per_seq
+    tables = np.random.default_rng(5).permutation(n_blocks).astype(np.int32).reshape(n_questions, blocks_per_seq)
+
+    def role(name, shape, seed, lm):
+        m = replace(shape, vocab=vocab)
+        weights = W.make_weights(m, seed, "cuda")
+        model = harness.make_model(m, weights, has_router_head=not lm)
+        dims = (n_blocks, m.n_kv_heads, m.kv_block, m.head_dim)
+        kv = A.KVCache([torch.zeros(dims, dtype=torch.bfloat16, device="cuda") for _ in range(m.n_layers)],
+                       [torch.zeros(dims, dtype=torch.bfloat16, device="cuda") for _ in range(m.n_layers)])
+        w_lm = W.normal_bf16(seed, "lm_head", (m.vocab, m.d_model), 0.02, "cuda") if lm else None
+        return Role(name, model, kv, w_lm)
+
+    roles = {"draft": role("draft", W.C2.model, 11, True), "target": role("target", W.C3.model, 12, True),
+             "router": role("router", W.C2.model, 13, False)}
+    questions = [[int(t) for t in W.uniform_ints(21, f"q{b}", prompt, vocab).numpy()] for b in range(n_questions)]
+
+    def run(tau, sep, steps):
+        for r in roles.values():
+            r.fed = {}
+        trace = []
+        arb = Arbitrage(roles["draft"], roles["target"], roles["router"], tables, tau=tau, sep=sep, eos=-5,
+                        max_step_tokens=max_step_tokens, trace=trace)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out, log = arb.run(questions, steps)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, out, log, trace
+
+    _, _, log0, trace0 = run(1e9, -7, 1)                       # probe (also the warm-up)
+    drafted = [e[4] for e in trace0 if e[0] == "step" and e[1] == "draft"]
+    sep = drafted[0][min(5, len(drafted[0]) - 1)]
+    tau = float(np.median([sc for b in log0 for sc, _ in log0[b]]))
+    dt, out, log, trace = run(tau, sep, alg_steps)
+    n_steps = sum(len(v) for v in log.values())
+    n_esc = sum(e for v in log.values() for _, e in v)
+    gen = sum(len(e[4]) for e in trace if e[0] == "step")
+    for r in roles.values():
+        r.model.close()
+    return {"steps_per_s": n_steps / dt, "generated_tokens_per_s": gen / dt, "seconds": dt, "questions": n_questions,
+            "prompt_tokens": prompt, "max_step_tokens": max_step_tokens, "alg1_steps": n_steps, "escalated": int(n_esc),
+            "generated_tokens": gen, "mean_step_tokens": gen / max(1, sum(1 for e in trace if e[0] == "step")),
+            "roles": "draft 1.5B shape, target 8B shape, router 1.5B shape + linear head; random-init, bf16"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +295,7 @@ def main():
     ap.add_argument("--breakdown", action="store_true", help="kept for compatibility: stage times are always reported")
     ap.add_argument("--stage-reps", type=int, default=3, help="extra passes per stage for the per-stage times (0: none, "
                     "for hardware-counter runs; per_config then holds the step times only)")
+    ap.add_argument("--alg1", type=int, default=1, help="1: also time Algorithm 1 end to end on three synthetic roles (field alg1)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the warm-up, run one plain device copy of this many MiB (a kernel of known traffic "
                          "that hardware-counter runs are scaled by)")
@@ -278,6 +342,9 @@ def main():
         out["gemm_mfma_frac"] = {e["workload"].split("-")[0]: round(e["gemm"]["aggregate_mfma_frac"], 4) for e in per_config}
     if "cpu_baseline" in head:
         out["cpu_baseline"] = head["cpu_baseline"]
+    if args.alg1 and args.stage_reps > 0:
+        out["alg1"] = run_alg1()
+        print(f"bench: Algorithm 1 done: {out['alg1']['steps_per_s']:.1f} steps per second", file=sys.stderr, flush=True)
     print(json.dumps(out))
 
 

@@ -228,6 +228,31 @@ arb_status arb_next_token(const void *hidden, const int32_t *rows, int32_t n, in
 arb_status arb_first_stop(const int32_t *tokens, int32_t n, int32_t max_len, int32_t sep, int32_t eos, int32_t *len,
                           uint8_t *ended, void *stream);
 
+/* One decoding iteration of n steps that are generated token by token (Alg. 1: a step ends with the first
+ * separator or end-of-sequence token; here also when it is max_len tokens long).  State, all on the device and
+ * owned by the caller, zero-initialised before a step's first iteration:
+ *   steps  int32 [n, max_len]  the tokens generated so far (row i valid up to len[i])
+ *   len    int32 [n]           tokens in each step so far
+ *   done   uint8 [n]           0 = open, 1 = ended by a separator or by reaching max_len, 2 = ended by eos
+ * open_rows (device int32 [n_open], ascending, each in [0, n), len < max_len, done = 0) lists the rows that were
+ * fed this iteration and chosen (device int32 [n_open]) the token arb_next_token chose for each.  The call appends
+ * every token to its row and updates len and done; the rows that stay open are written in ascending order to
+ * next_rows (device int32 [n_open]) and their tokens, the next iteration's input ids, to next_ids (device int32
+ * [n_open]); *n_next (device int32) is their number.  The host reads n_next and next_rows back to build the next
+ * iteration's batch: finished steps cost no further forward work and the loop ends when none is open; the tokens
+ * themselves never leave the device inside a step.  Rows outside open_rows are not touched.
+ * Errors: ARB_EINVAL for negative sizes, n_open > n, max_len <= 0 or a null pointer (n_next always required). */
+arb_status arb_step_advance(const int32_t *open_rows, const int32_t *chosen, int32_t n_open, int32_t n, int32_t max_len,
+                            int32_t sep, int32_t eos, int32_t *steps, int32_t *len, uint8_t *done, int32_t *next_rows,
+                            int32_t *next_ids, int32_t *n_next, void *stream);
+
+/* The generated steps of rows[0 .. n_rows) as one ragged token list, the form arb_score_steps and arb_prefill take
+ * (Alg. 1: the router scores the draft step z_d, the chosen step is appended to the context): ids[cu[j] + i] =
+ * steps[rows[j]][i] for i < cu[j+1] - cu[j].  steps device int32 [*, max_len] as above, rows device int32
+ * [n_rows], cu device int32 [n_rows + 1] (the batch's cu_step_lens), ids device int32 [cu[n_rows]]. */
+arb_status arb_pack_steps(const int32_t *steps, int32_t max_len, const int32_t *rows, const int32_t *cu, int32_t n_rows,
+                          int32_t *ids, void *stream);
+
 /* Pool slot of every step token, slot = block_tables[b][pos/kv_block]*kv_block + pos%kv_block with
  * pos = prefix_lens[b] + i, as the forward computes it.  slots: device int32 [total_tokens]. */
 arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream);

@@ -28,7 +28,7 @@ _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4:
 NOALLOC_SCRATCH_BYTES = 64 << 20      # ARB_NOALLOC_SCRATCH_BYTES of include/arb.h
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_score_steps_noalloc", "arb_prefill",
-           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_pack_k_blocked", "arb_w4_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
+           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_step_advance", "arb_pack_steps", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_pack_k_blocked", "arb_w4_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
            "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
@@ -95,6 +95,9 @@ def load_library(path: Optional[str] = None):
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.arb_first_stop.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_void_p]
+    lib.arb_step_advance.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.arb_pack_steps.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_slot_mapping.argtypes = [C.POINTER(_Batch), C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_int32, C.c_void_p]
@@ -344,6 +347,33 @@ def arb_first_stop(tokens: torch.Tensor, sep: int, eos: int, stream=None):
     _check(load_library().arb_first_stop(_ptr(tokens), n, S, int(sep), int(eos), _ptr(length), _ptr(ended),
                                          _stream(stream)))
     return length, ended
+
+
+def arb_step_advance(open_rows: torch.Tensor, chosen: torch.Tensor, steps: torch.Tensor, length: torch.Tensor,
+                     done: torch.Tensor, sep: int, eos: int, next_buf: torch.Tensor, next_ids: torch.Tensor, stream=None):
+    """One decoding iteration: appends chosen[j] to row open_rows[j] of steps (int32 [n, max_len]; length int32 [n],
+    done uint8 [n] updated in place).  next_buf int32 [1 + n_open]: element 0 receives the number of rows that stay
+    open, the elements behind it those rows; next_ids int32 [n_open] receives their tokens."""
+    for t in (open_rows, chosen, steps, length, next_buf, next_ids):
+        _dev(t, torch.int32)
+    _dev(done, torch.uint8)
+    n, S = steps.shape
+    n_open = open_rows.numel()
+    if chosen.numel() != n_open or next_buf.numel() < 1 + n_open or next_ids.numel() < n_open:
+        raise ValueError("arb_step_advance: buffer sizes")
+    _check(load_library().arb_step_advance(_ptr(open_rows), _ptr(chosen), n_open, n, S, int(sep), int(eos), _ptr(steps),
+                                           _ptr(length), _ptr(done), next_buf.data_ptr() + 4, _ptr(next_ids),
+                                           next_buf.data_ptr(), _stream(stream)))
+
+
+def arb_pack_steps(steps: torch.Tensor, rows: torch.Tensor, cu: torch.Tensor, total: int, stream=None) -> torch.Tensor:
+    """-> ids int32 [total]: the steps of `rows` (tokens steps[r][: cu[j+1] - cu[j]]) one after the other."""
+    for t in (steps, rows, cu):
+        _dev(t, torch.int32)
+    ids = torch.empty(total, dtype=torch.int32, device=steps.device)
+    _check(load_library().arb_pack_steps(_ptr(steps), steps.shape[1], _ptr(rows), _ptr(cu), rows.numel(), _ptr(ids),
+                                         _stream(stream)))
+    return ids
 
 
 def arb_slot_mapping(batch: DeviceBatch, kv_block: int = 16, stream=None) -> torch.Tensor:

@@ -497,6 +497,27 @@ extern "C" arb_status arb_first_stop(const int32_t *tokens, int32_t n, int32_t m
   return launch_first_stop(tokens, n, max_len, sep, eos, len, ended, (hipStream_t)stream);
 }
 
+extern "C" arb_status arb_step_advance(const int32_t *open_rows, const int32_t *chosen, int32_t n_open, int32_t n,
+                                       int32_t max_len, int32_t sep, int32_t eos, int32_t *steps, int32_t *len,
+                                       uint8_t *done, int32_t *next_rows, int32_t *next_ids, int32_t *n_next,
+                                       void *stream) {
+  if (n < 0 || n_open < 0 || n_open > n || max_len <= 0)
+    return arb_fail(ARB_EINVAL, "arb_step_advance: n = %d, n_open = %d, max_len = %d", n, n_open, max_len);
+  if (!n_next) return arb_fail(ARB_EINVAL, "arb_step_advance: null pointer");
+  if (n_open > 0 && (!open_rows || !chosen || !steps || !len || !done || !next_rows || !next_ids))
+    return arb_fail(ARB_EINVAL, "arb_step_advance: null pointer");
+  return launch_step_advance(open_rows, chosen, n_open, max_len, sep, eos, steps, len, done, next_rows, next_ids, n_next,
+                             (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_pack_steps(const int32_t *steps, int32_t max_len, const int32_t *rows, const int32_t *cu,
+                                     int32_t n_rows, int32_t *ids, void *stream) {
+  if (n_rows < 0 || max_len <= 0) return arb_fail(ARB_EINVAL, "arb_pack_steps: n_rows = %d, max_len = %d", n_rows, max_len);
+  if (n_rows == 0) return ARB_OK;
+  if (!steps || !rows || !cu || !ids) return arb_fail(ARB_EINVAL, "arb_pack_steps: null pointer");
+  return launch_pack_steps(steps, max_len, rows, cu, n_rows, ids, (hipStream_t)stream);
+}
+
 extern "C" arb_status arb_slot_mapping(const arb_batch *batch, int32_t kv_block, int32_t *slots, void *stream) {
   BatchInfo info;
   if (kv_block <= 0) return arb_fail(ARB_EINVAL, "arb_slot_mapping: kv_block %d", kv_block);

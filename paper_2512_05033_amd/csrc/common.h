@@ -132,6 +132,11 @@ arb_status launch_sample_token(const float *logits, int n, int V, float temperat
                                int32_t *token, float *chosen, hipStream_t st);
 arb_status launch_first_stop(const int32_t *tokens, int n, int S, int sep, int eos, int32_t *len, uint8_t *ended,
                              hipStream_t st);
+arb_status launch_step_advance(const int32_t *open_rows, const int32_t *chosen, int n_open, int S, int sep, int eos,
+                               int32_t *steps, int32_t *len, uint8_t *done, int32_t *next_rows, int32_t *next_ids,
+                               int32_t *n_next, hipStream_t st);
+arb_status launch_pack_steps(const int32_t *steps, int S, const int32_t *rows, const int32_t *cu, int n_rows, int32_t *ids,
+                             hipStream_t st);
 
 // gemm_w4.hip: 4-bit weights (offset-binary nibbles, eight k per uint32, bf16 scale per row and 128 k)
 arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, hipStream_t st);

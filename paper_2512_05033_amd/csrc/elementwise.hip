@@ -630,3 +630,73 @@ arb_status launch_first_stop(const int32_t *tokens, int n, int S, int sep, int e
   return ARB_OK;
 }
 
+// One decoding iteration of steps that are generated token by token (Alg. 1: a step ends with its first
+// separator or end-of-sequence token, or at S tokens).  Row r = open_rows[j] was fed this iteration and chose
+// chosen[j]: the token is appended, len and done are updated, and the rows that stay open are written in
+// order to next_rows with their tokens in next_ids (the ids of the next iteration).  One workgroup walks the
+// open rows 256 at a time; the order-preserving compaction is a ballot per wave plus a scan over the waves.
+__global__ __launch_bounds__(256) void step_advance_kernel(const int32_t *__restrict__ open_rows,
+                                                           const int32_t *__restrict__ chosen, int n_open, int S, int sep,
+                                                           int eos, int32_t *__restrict__ steps, int32_t *__restrict__ len,
+                                                           uint8_t *__restrict__ done, int32_t *__restrict__ next_rows,
+                                                           int32_t *__restrict__ next_ids, int32_t *__restrict__ n_next) {
+  __shared__ int wave_count[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int base = 0;                                  // rows kept by the chunks before this one
+  for (int j0 = 0; j0 < n_open; j0 += 256) {
+    const int j = j0 + threadIdx.x;
+    bool keep = false;
+    int r = 0, t = 0;
+    if (j < n_open) {
+      r = open_rows[j];
+      t = chosen[j];
+      const int l = len[r];
+      steps[(size_t)r * S + l] = t;
+      len[r] = l + 1;
+      const bool stop = t == sep || t == eos || l + 1 >= S;
+      done[r] = stop ? (t == eos ? 2 : 1) : 0;
+      keep = !stop;
+    }
+    const unsigned long long mask = __builtin_amdgcn_ballot_w64(keep);
+    if (lane == 0) wave_count[wave] = __builtin_popcountll(mask);
+    __syncthreads();
+    int before = base;
+    for (int w = 0; w < wave; ++w) before += wave_count[w];
+    if (keep) {
+      const int pos = before + __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+      next_rows[pos] = r;
+      next_ids[pos] = t;
+    }
+    base += wave_count[0] + wave_count[1] + wave_count[2] + wave_count[3];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *n_next = base;
+}
+
+arb_status launch_step_advance(const int32_t *open_rows, const int32_t *chosen, int n_open, int S, int sep, int eos,
+                               int32_t *steps, int32_t *len, uint8_t *done, int32_t *next_rows, int32_t *next_ids,
+                               int32_t *n_next, hipStream_t st) {
+  hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(256), 0, st, open_rows, chosen, n_open, S, sep, eos, steps, len,
+                     done, next_rows, next_ids, n_next);
+  ARB_CHECK_LAUNCH("step_advance");
+  return ARB_OK;
+}
+
+// ids[cu[j] + i] = steps[rows[j]][i] for i < cu[j+1] - cu[j]: the steps of the listed rows as one ragged token list
+__global__ __launch_bounds__(256) void pack_steps_kernel(const int32_t *__restrict__ steps, int S,
+                                                         const int32_t *__restrict__ rows, const int32_t *__restrict__ cu,
+                                                         int n_rows, int32_t *__restrict__ ids) {
+  const int j = blockIdx.x;
+  if (j >= n_rows) return;
+  const int r = rows[j], begin = cu[j], n = min(cu[j + 1] - begin, S);
+  for (int i = threadIdx.x; i < n; i += blockDim.x) ids[begin + i] = steps[(size_t)r * S + i];
+}
+
+arb_status launch_pack_steps(const int32_t *steps, int S, const int32_t *rows, const int32_t *cu, int n_rows, int32_t *ids,
+                             hipStream_t st) {
+  if (n_rows == 0) return ARB_OK;
+  hipLaunchKernelGGL(pack_steps_kernel, dim3(n_rows), dim3(256), 0, st, steps, S, rows, cu, n_rows, ids);
+  ARB_CHECK_LAUNCH("pack_steps");
+  return ARB_OK;
+}
+

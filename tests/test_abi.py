@@ -120,6 +120,14 @@ def test_batch_validation_happens_on_the_host(lib):
     assert lib.arb_budget_threshold(0x1000, -1, 0, 0x1000, None) == B.ARB_EINVAL
     assert lib.arb_budget_threshold(0x1000, 4, 1, None, None) == B.ARB_EINVAL
     assert lib.arb_stage_layers(None, None, None, 0, 1, None, None, None, 0, None) == B.ARB_EINVAL
+    # step bookkeeping of the decode loop
+    assert lib.arb_step_advance(None, None, 0, 4, 8, 1, 2, None, None, None, None, None, None, None) == B.ARB_EINVAL   # no n_next
+    assert lib.arb_step_advance(0x1000, 0x1000, 5, 4, 8, 1, 2, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, None) == B.ARB_EINVAL
+    assert lib.arb_step_advance(0x1000, 0x1000, 2, 4, 0, 1, 2, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, None) == B.ARB_EINVAL
+    assert lib.arb_step_advance(0x1000, None, 2, 4, 8, 1, 2, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, None) == B.ARB_EINVAL
+    assert lib.arb_pack_steps(None, 8, None, None, 0, None, None) == B.ARB_OK
+    assert lib.arb_pack_steps(0x1000, 0, 0x1000, 0x1000, 2, 0x1000, None) == B.ARB_EINVAL
+    assert lib.arb_pack_steps(0x1000, 8, None, 0x1000, 2, 0x1000, None) == B.ARB_EINVAL
     assert lib.arb_stage_gemm(0x1000, 0x1000, None, 0x1000, 8, 128, 96, 0, None) == B.ARB_EUNSUPPORTED
     assert lib.arb_stage_gemm(0x1000, 0x1000, None, 0x1000, 8, 100, 128, 0, None) == B.ARB_EUNSUPPORTED
     lib.arb_model_destroy(h)

@@ -760,6 +760,43 @@ def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A):
 
 # ------------------------------------------------------------------ Algorithm 1 loop
 
+@pytest.mark.parametrize("n,S,vocab", [(5, 7, 6), (700, 12, 9), (64, 1, 3)])
+def test_step_advance_and_pack_follow_first_stop(A, n, S, vocab):
+    """Token columns fed one iteration at a time: every step must end where the oracle's first_stop puts its end
+    (separator, eos, or max_len), hold exactly those tokens, and drop out of the open list from then on; the
+    packed ragged list must be the concatenation of the steps."""
+    sep, eos = 1, 2
+    toks = np.random.default_rng(n).integers(0, vocab, size=(n, S)).astype(np.int32)
+    dev = "cuda"
+    steps = torch.zeros(n, S, dtype=torch.int32, device=dev)
+    length = torch.zeros(n, dtype=torch.int32, device=dev)
+    done = torch.zeros(n, dtype=torch.uint8, device=dev)
+    next_buf = torch.empty(1 + n, dtype=torch.int32, device=dev)
+    next_ids = torch.empty(n, dtype=torch.int32, device=dev)
+    open_rows = list(range(n))
+    all_toks = torch.from_numpy(toks).to(dev)
+    for i in range(S):
+        if not open_rows:
+            break
+        rows_dev = torch.tensor(open_rows, dtype=torch.int32, device=dev)
+        chosen = all_toks[rows_dev.long(), i].contiguous()
+        A.arb_step_advance(rows_dev, chosen, steps, length, done, sep, eos, next_buf, next_ids)
+        nb = next_buf.cpu().numpy()
+        want_open = [r for r in open_rows if toks[r, i] not in (sep, eos) and i + 1 < S]
+        assert int(nb[0]) == len(want_open) and nb[1:1 + nb[0]].tolist() == want_open
+        assert next_ids[:len(want_open)].cpu().numpy().tolist() == [int(toks[r, i]) for r in want_open]
+        open_rows = want_open
+    got, gl, gd = steps.cpu().numpy(), length.cpu().numpy(), done.cpu().numpy()
+    for r in range(n):
+        L, ended = O.first_stop([int(t) for t in toks[r]], sep, eos)
+        assert gl[r] == L and got[r, :L].tolist() == toks[r, :L].tolist() and (got[r, L:] == 0).all()
+        assert gd[r] == (2 if ended else 1)
+    rows = np.random.default_rng(1).permutation(n)[: max(1, n // 2)].astype(np.int32)
+    cu = np.concatenate([[0], np.cumsum(gl[rows])]).astype(np.int32)
+    ids = A.arb_pack_steps(steps, torch.from_numpy(rows).to(dev), torch.from_numpy(cu).to(dev), int(cu[-1])).cpu().numpy()
+    assert ids.tolist() == [int(t) for r in rows for t in toks[r, :gl[r]]]
+
+
 def _tiny_role(A, name, seed, n_blocks, with_lm):
     from paper_2512_05033_amd.arbitrage import Role
     m = W.TINY
