@@ -17,6 +17,7 @@ namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64, GROUP = 128;
 constexpr int LDS_TILE = BM * BK;
+constexpr int kSkinnyRows = 32;     // up to this many activation rows the weight-streaming kernel runs
 
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -229,6 +230,127 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict_
   }
 }
 
+
+// Few tokens (M <= 32: drafting token by token): the product is bound by streaming the packed weights once,
+// so there is no tile of A to share and no LDS stage.  A workgroup owns 64 weight rows (SwiGLU: 32 gate rows
+// and the 32 up rows of the same features) and a K range; its four waves take the 128-wide groups of that range
+// in turn and each multiplies whole groups: a lane fetches the 32 + 32 bytes of its two weight rows (one per
+// 32-row block) and of a group half straight from memory, two groups ahead, expands them in registers and feeds
+// them to the MFMAs as the column operand, against activation fragments read from the (cache-resident) A
+// rows one group ahead.  Within a group lane half h owns k = 64 h .. 64 h + 63, eight per MFMA step: the
+// contraction order is free as long as both operands agree.  The four partial results meet in LDS for the
+// epilogue.  Same arithmetic as the tile kernel: integer weights in the MFMAs, one fp32 multiply by the
+// group's scale per group.
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__restrict__ A, const uint32_t *__restrict__ Bq,
+                                                                const bf16 *__restrict__ Bscale, void *__restrict__ Cv,
+                                                                int M, int N, int K) {
+  __shared__ float part[4][2][16][64];                 // [wave][row block][accumulator register][lane]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int tile = blockIdx.x;
+  const uint32_t *bq[2];
+  const bf16 *sc[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = EPI == ARB_EPI_SWIGLU_BF16 ? (j ? N : 0) + tile * 32 + col : tile * 64 + j * 32 + col;
+    bq[j] = Bq + (size_t)row * (K / 8) + half * 8;
+    sc[j] = Bscale + (size_t)row * (K / GROUP);
+  }
+  const bf16 *a_row = A + (size_t)(col < M ? col : M - 1) * K + half * 64;    // rows past M re-read the last one; never stored
+
+  const int ng_all = K / GROUP;
+  const int g_begin = (int)((long long)ng_all * blockIdx.y / gridDim.y);
+  const int g_end = (int)((long long)ng_all * (blockIdx.y + 1) / gridDim.y);
+
+  f32x16 acc[2], tmp[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = tmp[j][r] = 0.f;
+
+  auto load_w = [&](int g, u32x4 (&w)[2][2]) {
+    g = g < g_end ? g : g_end - 1;                       // past the range: a valid group, not used
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      w[j][0] = *(const u32x4 *)(bq[j] + (size_t)g * 16);
+      w[j][1] = *(const u32x4 *)(bq[j] + (size_t)g * 16 + 4);
+    }
+  };
+  auto load_a = [&](int g, bf16x8 (&a)[8]) {
+    g = g < g_end ? g : g_end - 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = *(const bf16x8 *)(a_row + (size_t)g * GROUP + i * 8);
+  };
+
+  int g = g_begin + wave;
+  if (g < g_end) {
+    u32x4 w0[2][2], w1[2][2], w2[2][2];
+    bf16x8 a0[8], a1[8];
+    load_w(g, w0);
+    load_a(g, a0);
+    load_w(g + 4, w1);
+    auto group = [&](int gg, u32x4 (&w)[2][2], u32x4 (&w_far)[2][2], bf16x8 (&a)[8], bf16x8 (&a_next)[8]) {
+      load_w(gg + 8, w_far);
+      load_a(gg + 4, a_next);
+      const float s0 = (float)sc[0][gg], s1 = (float)sc[1][gg];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], expand_nibbles(w[0][i >> 2][i & 3]), tmp[0], 0, 0, 0);
+        tmp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], expand_nibbles(w[1][i >> 2][i & 3]), tmp[1], 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc[0][r] = fmaf(tmp[0][r], s0, acc[0][r]);
+        acc[1][r] = fmaf(tmp[1][r], s1, acc[1][r]);
+        tmp[0][r] = 0.f;
+        tmp[1][r] = 0.f;
+      }
+    };
+    // three groups per turn so that the register sets rotate without copies
+    for (; g < g_end; g += 24) {
+      group(g, w0, w2, a0, a1);
+      if (g + 4 >= g_end) break;
+      group(g + 4, w1, w0, a1, a0);
+      if (g + 8 >= g_end) break;
+      group(g + 8, w2, w1, a0, a1);
+      if (g + 12 >= g_end) break;
+      group(g + 12, w0, w2, a1, a0);
+      if (g + 16 >= g_end) break;
+      group(g + 16, w1, w0, a0, a1);
+      if (g + 20 >= g_end) break;
+      group(g + 20, w2, w1, a1, a0);
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave][j][r][lane] = acc[j][r];
+  __syncthreads();
+  // D layout of the 32x32 MFMA: lane holds column lane%32 (a weight row) and rows (tokens) 8*(r/4) + 4*(lane/32) + r%4.
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int idx = tid + 256 * p, r = idx >> 6, L = idx & 63;
+    const int m = 8 * (r >> 2) + 4 * (L >> 5) + (r & 3), c = L & 31;
+    float v[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) v[j] = (part[0][j][r][L] + part[1][j][r][L]) + (part[2][j][r][L] + part[3][j][r][L]);
+    if (m >= M) continue;
+    if (EPI == ARB_EPI_SWIGLU_BF16) {
+      ((bf16 *)Cv)[(size_t)m * N + tile * 32 + c] = (bf16)(v[0] * __builtin_amdgcn_rcpf(1.0f + __expf(-v[0])) * v[1]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const size_t at = (size_t)m * N + tile * 64 + j * 32 + c;
+        if (EPI == ARB_EPI_STORE_BF16) ((bf16 *)Cv)[at] = (bf16)v[j];
+        else if (EPI == EPI_PARTIAL_F32) ((float *)Cv)[(size_t)blockIdx.y * M * N + at] = v[j];
+        else ((float *)Cv)[at] += v[j];
+      }
+    }
+  }
+}
+
 }  // namespace
 
 arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, hipStream_t st) {
@@ -257,8 +379,13 @@ arb_status launch_gemm_w4(const bf16 *A, const uint32_t *Bq, const bf16 *Bscale,
   if (splits > 1 && epilogue != ARB_EPI_RESIDUAL_F32 && epilogue != ARB_EPI_STORE_F32)
     return arb_fail(ARB_EINVAL, "gemm_w4: split-K needs an fp32 epilogue (partial products)");
   if (splits < 1 || splits > K / GROUP) return arb_fail(ARB_EINVAL, "gemm_w4: %d splits of %d groups", splits, K / GROUP);
-  const dim3 grid(tiles_m * tiles_n, splits), block(256);
-#define ARB_W4(E) hipLaunchKernelGGL((gemm_w4_kernel<E>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K, tiles_m, tiles_n)
+  const bool skinny = M <= kSkinnyRows;                // few tokens: the weight-streaming kernel, 64 weight rows per workgroup
+  const dim3 grid(skinny ? (epilogue == ARB_EPI_SWIGLU_BF16 ? N / 32 : N / 64) : tiles_m * tiles_n, splits), block(256);
+#define ARB_W4(E)                                                                                                    \
+  do {                                                                                                               \
+    if (skinny) hipLaunchKernelGGL((gemm_w4_skinny_kernel<E>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K);       \
+    else hipLaunchKernelGGL((gemm_w4_kernel<E>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K, tiles_m, tiles_n);   \
+  } while (0)
   switch (epilogue) {
     case ARB_EPI_STORE_BF16: ARB_W4(ARB_EPI_STORE_BF16); break;
     case ARB_EPI_RESIDUAL_F32:

@@ -4,6 +4,8 @@ the same seeded inputs.  Tolerances: hidden states max|d|/max|ref| <= 2e-2
 multiple of the bf16-operand floor the oracle measures on the same sample), router
 scores |d| <= 1e-2, decisions identical unless |score - tau| < 1e-2, slot
 indices and untouched cache contents bit-exact."""
+from dataclasses import replace
+
 import numpy as np
 import pytest
 import torch
@@ -713,7 +715,10 @@ def test_w4_quantize_bit_exact(A, N, K):
 
 @pytest.mark.parametrize("M,N,K,epi", [(1, 128, 128, "store"), (16, 1536, 8960, "f32"), (200, 2048, 1536, "store"),
                                        (130, 8960, 1536, "swiglu"), (333, 1536, 1536, "residual"),
-                                       (1024, 4480, 1536, "swiglu")])
+                                       (1024, 4480, 1536, "swiglu"),
+                                       # up to 32 rows the weight-streaming kernel runs (33: the tile kernel again)
+                                       (32, 2048, 4096, "store"), (7, 8960, 1536, "swiglu"), (32, 256, 1536, "residual"),
+                                       (5, 256, 384, "f32"), (33, 256, 1536, "residual"), (17, 14336, 4096, "swiglu")])
 def test_w4_gemm(A, M, N, K, epi):
     rows = 2 * N if epi == "swiglu" else N
     a, w = rand_bf16((M, K), 1.0, 52), rand_bf16((rows, K), 0.05, 53)
@@ -736,10 +741,13 @@ def test_w4_gemm(A, M, N, K, epi):
         assert got.shape == (M, N) and rel_err(got, O.silu(ref[:, :N]) * ref[:, N:]) < 5e-3
 
 
-def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A):
+@pytest.mark.parametrize("few_tokens", [False, True])
+def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A, few_tokens):
     """The whole forward with 4-bit projection weights (C2's shape, 2 layers, so that split-K, SwiGLU
     and the plain epilogue all run on packed weights) against the oracle given the dequantized values."""
     w = W.scaled(W.C2, n_layers=2, batch=4)
+    if few_tokens:                       # 4 sequences x 5 tokens: every projection on the weight-streaming kernel
+        w = replace(w, step=("fixed", 5, 5))
     batch = W.make_batch(w)
     weights = W.make_weights(w.model, w.seed, "cuda", gain_jitter=0.1)
     qw = A.QuantizedWeights(weights)
