@@ -18,6 +18,7 @@ namespace {
 constexpr int BM = 128, BN = 128, BK = 64, GROUP = 128;
 constexpr int LDS_TILE = BM * BK;
 constexpr int kSkinnyRows = 32;     // up to this many activation rows the weight-streaming kernel runs
+constexpr int kSkinnyAhead = 3;     // groups of packed weights a wave of that kernel has in flight
 
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -35,6 +36,30 @@ __device__ __forceinline__ bf16x8 expand_nibbles(uint32_t w) {
     const float f = __uint_as_float(0x4B000000u | ((w >> (4 * e)) & 15u)) - 8388616.0f;
     o[e] = (bf16)f;
   }
+  return o;
+}
+
+// The same eight nibbles as the bf16 integers 16 * (nibble - 8), with half the instructions: nibble ^ 8 is the
+// two's-complement form of nibble - 8, and in the high half of a byte it is the signed byte 16 * (nibble - 8),
+// which one conversion with a sign-extending byte select turns into a float.  The factor 16 goes into the
+// group's scale.
+template <int BYTE>
+__device__ __forceinline__ float signed_byte_to_float(uint32_t x) {
+  float f;
+  if (BYTE == 0) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(f) : "v"(x));
+  if (BYTE == 1) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(f) : "v"(x));
+  if (BYTE == 2) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(f) : "v"(x));
+  if (BYTE == 3) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(f) : "v"(x));
+  return f;
+}
+__device__ __forceinline__ bf16x8 expand_nibbles_x16(uint32_t w) {
+  const uint32_t t = w ^ 0x88888888u;
+  const uint32_t even = (t << 4) & 0xF0F0F0F0u, odd = t & 0xF0F0F0F0u;      // nibbles 0,2,4,6 / 1,3,5,7 as signed bytes
+  bf16x8 o;
+  o[0] = (bf16)signed_byte_to_float<0>(even); o[1] = (bf16)signed_byte_to_float<0>(odd);
+  o[2] = (bf16)signed_byte_to_float<1>(even); o[3] = (bf16)signed_byte_to_float<1>(odd);
+  o[4] = (bf16)signed_byte_to_float<2>(even); o[5] = (bf16)signed_byte_to_float<2>(odd);
+  o[6] = (bf16)signed_byte_to_float<3>(even); o[7] = (bf16)signed_byte_to_float<3>(odd);
   return o;
 }
 
@@ -235,20 +260,28 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict_
 // so there is no tile of A to share and no LDS stage.  A workgroup owns 64 weight rows (SwiGLU: 32 gate rows
 // and the 32 up rows of the same features) and a K range; its four waves take the 128-wide groups of that range
 // in turn and each multiplies whole groups: a lane fetches the 32 + 32 bytes of its two weight rows (one per
-// 32-row block) and of a group half straight from memory, two groups ahead, expands them in registers and feeds
-// them to the MFMAs as the column operand, against activation fragments read from the (cache-resident) A
-// rows one group ahead.  Within a group lane half h owns k = 64 h .. 64 h + 63, eight per MFMA step: the
+// 32-row block) and of a group half straight from memory, several groups ahead, expands them in registers and
+// feeds them to the MFMAs as the column operand, against activation fragments from a tile of its own in LDS,
+// loaded one group ahead (fetched straight into registers, 16 bytes per lane from up to 32 rows, the time grew
+// with the number of rows: 30 us at one row, 38 us at 32 on the 8B gate/up shape; staged, 30-33 us at any).  Within a group lane half h owns k = 64 h .. 64 h + 63, eight per MFMA step: the
 // contraction order is free as long as both operands agree.  The four partial results meet in LDS for the
-// epilogue.  Same arithmetic as the tile kernel: integer weights in the MFMAs, one fp32 multiply by the
-// group's scale per group.
+// epilogue.  Same arithmetic as the tile kernel: integer weights in the MFMAs (here 16 q, exact in bf16), one
+// fp32 multiply by the group's scale (here scale / 16, exact) per group.
 template <int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__restrict__ A, const uint32_t *__restrict__ Bq,
                                                                 const bf16 *__restrict__ Bscale, void *__restrict__ Cv,
                                                                 int M, int N, int K) {
-  __shared__ float part[4][2][16][64];                 // [wave][row block][accumulator register][lane]
+  // Activations: every wave stages the 32 x 128 tile of its group in a region of its own (8 KB per stage, two
+  // stages; one array per stage so that reads of one are not ordered behind the loads in flight into the other).
+  // After the loop the first stage array holds the partial results: [wave][row block][accumulator register][lane].
+  __shared__ __attribute__((aligned(16))) bf16 St0[4 * 32 * GROUP], St1[4 * 32 * GROUP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int tile = blockIdx.x;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int ng_all = K / GROUP;
+  const int g_begin = (int)((long long)ng_all * blockIdx.y / gridDim.y);
+  const int g_end = (int)((long long)ng_all * (blockIdx.y + 1) / gridDim.y);
   const uint32_t *bq[2];
   const bf16 *sc[2];
 #pragma unroll
@@ -257,11 +290,29 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
     bq[j] = Bq + (size_t)row * (K / 8) + half * 8;
     sc[j] = Bscale + (size_t)row * (K / GROUP);
   }
-  const bf16 *a_row = A + (size_t)(col < M ? col : M - 1) * K + half * 64;    // rows past M re-read the last one; never stored
-
-  const int ng_all = K / GROUP;
-  const int g_begin = (int)((long long)ng_all * blockIdx.y / gridDim.y);
-  const int g_end = (int)((long long)ng_all * (blockIdx.y + 1) / gridDim.y);
+  // A direct-to-LDS load moves four activation rows of the group (4 x 256 bytes, 16 lanes each); a row's sixteen
+  // 16-byte chunks land XORed with the row number so that the fragment reads (16 rows, one chunk) are free of
+  // bank conflicts.  Only the rows that exist are loaded: the others only feed output rows that are never stored.
+  const int n_dma = (M + 3) / 4;
+  const int dma_row = lane >> 4, dma_slot = lane & 15;
+  auto dma_a = [&](int g, int stage) {
+    g = g < g_end ? g : g_end - 1;
+    bf16 *dst = (stage ? St1 : St0) + wave_u * (32 * GROUP);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (j < n_dma) {
+        const int r = 4 * j + dma_row;
+        const bf16 *src = A + (size_t)(r < M ? r : M - 1) * K + (size_t)g * GROUP + ((dma_slot ^ (r & 15)) << 3);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(dst + j * 512), 16, 0, 0);
+      }
+    }
+  };
+  // fragment of MFMA step i: this lane's row, chunk 8 half + i
+  const int frag_off = col * GROUP;
+  auto frag_a = [&](int stage, int i) {
+    const bf16 *reg = (stage ? St1 : St0) + wave_u * (32 * GROUP);
+    return *(const bf16x8 *)&reg[frag_off + (((half * 8 + i) ^ (col & 15)) << 3)];
+  };
 
   f32x16 acc[2], tmp[2];
 #pragma unroll
@@ -269,60 +320,60 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = tmp[j][r] = 0.f;
 
-  auto load_w = [&](int g, u32x4 (&w)[2][2]) {
+  // the packed weights of a group and, with them, their scales: loads complete in order, so a scale fetched when it
+  // is needed would make the wave wait for everything requested before it
+  struct Fetched { u32x4 w[2][2]; bf16 s[2]; };
+  auto load_w = [&](int g, Fetched &f) {
     g = g < g_end ? g : g_end - 1;                       // past the range: a valid group, not used
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      w[j][0] = *(const u32x4 *)(bq[j] + (size_t)g * 16);
-      w[j][1] = *(const u32x4 *)(bq[j] + (size_t)g * 16 + 4);
+      f.w[j][0] = *(const u32x4 *)(bq[j] + (size_t)g * 16);
+      f.w[j][1] = *(const u32x4 *)(bq[j] + (size_t)g * 16 + 4);
+      f.s[j] = sc[j][g];
     }
   };
-  auto load_a = [&](int g, bf16x8 (&a)[8]) {
-    g = g < g_end ? g : g_end - 1;
+  // The weights of kAhead groups are in flight while one is multiplied (a ring of kAhead + 1 register sets, the
+  // loop unrolled over it so that every set has a fixed place); activations one group ahead.
+  constexpr int NW = kSkinnyAhead + 1;
+  static_assert(NW % 2 == 0, "the activation sets alternate inside the unrolled ring");
+  const int g_first = g_begin + wave;
+  if (g_first < g_end) {
+    Fetched f[NW];
+    dma_a(g_first, 0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a[i] = *(const bf16x8 *)(a_row + (size_t)g * GROUP + i * 8);
-  };
-
-  int g = g_begin + wave;
-  if (g < g_end) {
-    u32x4 w0[2][2], w1[2][2], w2[2][2];
-    bf16x8 a0[8], a1[8];
-    load_w(g, w0);
-    load_a(g, a0);
-    load_w(g + 4, w1);
-    auto group = [&](int gg, u32x4 (&w)[2][2], u32x4 (&w_far)[2][2], bf16x8 (&a)[8], bf16x8 (&a_next)[8]) {
-      load_w(gg + 8, w_far);
-      load_a(gg + 4, a_next);
-      const float s0 = (float)sc[0][gg], s1 = (float)sc[1][gg];
+    for (int d = 0; d < NW - 1; ++d) load_w(g_first + 4 * d, f[d]);
+    for (int base = g_first; base < g_end; base += 4 * NW) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], expand_nibbles(w[0][i >> 2][i & 3]), tmp[0], 0, 0, 0);
-        tmp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], expand_nibbles(w[1][i >> 2][i & 3]), tmp[1], 0, 0, 0);
+      for (int u = 0; u < NW; ++u) {
+        const int gg = base + 4 * u;
+        if (gg >= g_end) break;
+        // The activation tile of this group was requested before the latest set of weights (4 + 2 loads): once
+        // at most those are outstanding it has landed (loads complete in order; the wave reads only its own tile,
+        // so no barrier is needed).
+        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        dma_a(gg + 4, (u + 1) & 1);          // first: needed earlier than the weights requested below
+        load_w(gg + 4 * (NW - 1), f[(u + NW - 1) % NW]);
+        const Fetched &cur = f[u];
+        const float s0 = (float)cur.s[0] * 0.0625f, s1 = (float)cur.s[1] * 0.0625f;     // the weights come as 16 q
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bf16x8 fa = frag_a(u & 1, i);
+          tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_x16(cur.w[0][i >> 2][i & 3]), tmp[0], 0, 0, 0);
+          tmp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_x16(cur.w[1][i >> 2][i & 3]), tmp[1], 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          acc[0][r] = fmaf(tmp[0][r], s0, acc[0][r]);
+          acc[1][r] = fmaf(tmp[1][r], s1, acc[1][r]);
+          tmp[0][r] = 0.f;
+          tmp[1][r] = 0.f;
+        }
       }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        acc[0][r] = fmaf(tmp[0][r], s0, acc[0][r]);
-        acc[1][r] = fmaf(tmp[1][r], s1, acc[1][r]);
-        tmp[0][r] = 0.f;
-        tmp[1][r] = 0.f;
-      }
-    };
-    // three groups per turn so that the register sets rotate without copies
-    for (; g < g_end; g += 24) {
-      group(g, w0, w2, a0, a1);
-      if (g + 4 >= g_end) break;
-      group(g + 4, w1, w0, a1, a0);
-      if (g + 8 >= g_end) break;
-      group(g + 8, w2, w1, a0, a1);
-      if (g + 12 >= g_end) break;
-      group(g + 12, w0, w2, a1, a0);
-      if (g + 16 >= g_end) break;
-      group(g + 16, w1, w0, a0, a1);
-      if (g + 20 >= g_end) break;
-      group(g + 20, w2, w1, a1, a0);
     }
   }
 
+  __syncthreads();                                       // every wave is done with its stage reads
+  float (*part)[2][16][64] = (float (*)[2][16][64])St0;
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
