@@ -39,28 +39,31 @@ __device__ __forceinline__ bf16x8 expand_nibbles(uint32_t w) {
   return o;
 }
 
-// The same eight nibbles as the bf16 integers 16 * (nibble - 8), with half the instructions: nibble ^ 8 is the
-// two's-complement form of nibble - 8, and in the high half of a byte it is the signed byte 16 * (nibble - 8),
-// which one conversion with a sign-extending byte select turns into a float.  The factor 16 goes into the
-// group's scale.
-template <int BYTE>
-__device__ __forceinline__ float signed_byte_to_float(uint32_t x) {
-  float f;
-  if (BYTE == 0) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(f) : "v"(x));
-  if (BYTE == 1) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(f) : "v"(x));
-  if (BYTE == 2) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(f) : "v"(x));
-  if (BYTE == 3) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(f) : "v"(x));
-  return f;
+// Eight nibbles as the bf16 values 16 + nibble = 24 + q, without a conversion instruction (those run at a quarter
+// of the rate of plain integer instructions here, and sixteen of them per word bound the kernel): in the binade
+// [16, 32) a bf16 is 16 (1 + m / 128), so a nibble placed in the four top bits of the mantissa adds exactly its
+// value.  Two nibbles four apart are placed by one shift and one and-or, so the elements come out in the order
+// 0, 4, 1, 5, 2, 6, 3, 7 (the caller orders the other operand alike).  The constant 24 is taken out again in
+// fp32: sum_k a_k (24 + q_k) - 24 sum_k a_k, with the second sum from an MFMA against ones; the terms are about
+// five times the size of the result, so fp32 loses two or three more bits than without the detour, far below
+// what the rounding of the output, or an fp32 test bar of 1e-5, sees.
+__device__ __forceinline__ bf16x8 expand_nibbles_plus24(uint32_t w) {
+  u32x4 d;
+  d[0] = ((w << 3) & 0x00780078u) | 0x41804180u;
+  d[1] = ((w >> 1) & 0x00780078u) | 0x41804180u;
+  d[2] = ((w >> 5) & 0x00780078u) | 0x41804180u;
+  d[3] = ((w >> 9) & 0x00780078u) | 0x41804180u;
+  return __builtin_bit_cast(bf16x8, d);
 }
-__device__ __forceinline__ bf16x8 expand_nibbles_x16(uint32_t w) {
-  const uint32_t t = w ^ 0x88888888u;
-  const uint32_t even = (t << 4) & 0xF0F0F0F0u, odd = t & 0xF0F0F0F0u;      // nibbles 0,2,4,6 / 1,3,5,7 as signed bytes
-  bf16x8 o;
-  o[0] = (bf16)signed_byte_to_float<0>(even); o[1] = (bf16)signed_byte_to_float<0>(odd);
-  o[2] = (bf16)signed_byte_to_float<1>(even); o[3] = (bf16)signed_byte_to_float<1>(odd);
-  o[4] = (bf16)signed_byte_to_float<2>(even); o[5] = (bf16)signed_byte_to_float<2>(odd);
-  o[6] = (bf16)signed_byte_to_float<3>(even); o[7] = (bf16)signed_byte_to_float<3>(odd);
-  return o;
+// elements 0..7 -> 0, 4, 1, 5, 2, 6, 3, 7
+__device__ __forceinline__ bf16x8 interleave_halves(bf16x8 a) {
+  const u32x4 r = __builtin_bit_cast(u32x4, a);
+  u32x4 d;
+  d[0] = __builtin_amdgcn_perm(r[2], r[0], 0x05040100u);
+  d[1] = __builtin_amdgcn_perm(r[2], r[0], 0x07060302u);
+  d[2] = __builtin_amdgcn_perm(r[3], r[1], 0x05040100u);
+  d[3] = __builtin_amdgcn_perm(r[3], r[1], 0x07060302u);
+  return __builtin_bit_cast(bf16x8, d);
 }
 
 __global__ __launch_bounds__(256) void w4_quantize_kernel(const bf16 *__restrict__ W, int N, int K,
@@ -257,24 +260,31 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict_
 
 
 // Few tokens (M <= 32: drafting token by token): the product is bound by streaming the packed weights once,
-// so there is no tile of A to share and no LDS stage.  A workgroup owns 64 weight rows (SwiGLU: 32 gate rows
-// and the 32 up rows of the same features) and a K range; its four waves take the 128-wide groups of that range
-// in turn and each multiplies whole groups: a lane fetches the 32 + 32 bytes of its two weight rows (one per
-// 32-row block) and of a group half straight from memory, several groups ahead, expands them in registers and
-// feeds them to the MFMAs as the column operand, against activation fragments from a tile of its own in LDS,
-// loaded one group ahead (fetched straight into registers, 16 bytes per lane from up to 32 rows, the time grew
-// with the number of rows: 30 us at one row, 38 us at 32 on the 8B gate/up shape; staged, 30-33 us at any).  Within a group lane half h owns k = 64 h .. 64 h + 63, eight per MFMA step: the
-// contraction order is free as long as both operands agree.  The four partial results meet in LDS for the
-// epilogue.  Same arithmetic as the tile kernel: integer weights in the MFMAs (here 16 q, exact in bf16), one
-// fp32 multiply by the group's scale (here scale / 16, exact) per group.
-template <int EPI>
+// so there is no tile of A to share.  A workgroup owns 64 weight rows (SwiGLU: 32 gate rows and the 32 up
+// rows of the same features) and a K range; its four waves take the 128-wide groups of that range in turn and
+// each multiplies whole groups: a lane fetches the 32 + 32 bytes of its two weight rows (one per 32-row
+// block) and of a group half straight from memory, kSkinnyAhead groups ahead, expands them in registers and
+// feeds them to the MFMAs as the column operand, against activation fragments from a tile of the wave's own in
+// LDS (MR rows x 128, direct-to-LDS loads NS - 1 groups ahead; fetched straight into registers, 16 bytes per
+// lane from up to 32 rows, the time grew with the number of rows).  What bounds a wave is the chain of round
+// trips to memory, one per group it cannot request early enough: with the activations one group ahead the 8B
+// gate/up shape took 30 us whatever the expansion cost (three versions of it) and even with all weights
+// resident in L2; hence the deeper ring where the tile is small (16 rows: four stages).  Within a group lane
+// half h owns k = 64 h .. 64 h + 63, eight per MFMA step: the contraction order is free as long as both operands
+// agree.  The four partial results meet in LDS for the epilogue.  Arithmetic as in the tile kernel: integer
+// weights in the MFMAs (here 24 + q, see expand_nibbles_plus24), one fp32 multiply by the group's scale per group.
+template <int EPI, int MR, int NS>
 __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__restrict__ A, const uint32_t *__restrict__ Bq,
                                                                 const bf16 *__restrict__ Bscale, void *__restrict__ Cv,
                                                                 int M, int N, int K) {
-  // Activations: every wave stages the 32 x 128 tile of its group in a region of its own (8 KB per stage, two
-  // stages; one array per stage so that reads of one are not ordered behind the loads in flight into the other).
-  // After the loop the first stage array holds the partial results: [wave][row block][accumulator register][lane].
-  __shared__ __attribute__((aligned(16))) bf16 St0[4 * 32 * GROUP], St1[4 * 32 * GROUP];
+  static_assert((MR == 16 && NS == 4) || (MR == 32 && NS == 2), "64 KB of stages");
+  constexpr int NW = kSkinnyAhead + 1;                 // register sets of packed weights
+  static_assert(NW % NS == 0 && NW >= NS, "one unrolled ring for both");
+  constexpr int WAVE_TILE = MR * GROUP;                // elements of a wave's activation tile
+  // One array per stage, so that reads of one are not ordered behind the loads in flight into another.  After the
+  // loop the first arrays hold the partial results: per wave [row block][accumulator register][lane] floats (8 KB).
+  __shared__ __attribute__((aligned(16))) bf16 St0[4 * WAVE_TILE], St1[4 * WAVE_TILE], St2[NS > 2 ? 4 * WAVE_TILE : 8],
+      St3[NS > 2 ? 4 * WAVE_TILE : 8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int tile = blockIdx.x;
@@ -290,94 +300,134 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
     bq[j] = Bq + (size_t)row * (K / 8) + half * 8;
     sc[j] = Bscale + (size_t)row * (K / GROUP);
   }
+  auto stage = [&](int st) -> bf16 * {
+    return (st == 0 ? St0 : st == 1 ? St1 : st == 2 ? St2 : St3) + wave_u * WAVE_TILE;
+  };
   // A direct-to-LDS load moves four activation rows of the group (4 x 256 bytes, 16 lanes each); a row's sixteen
   // 16-byte chunks land XORed with the row number so that the fragment reads (16 rows, one chunk) are free of
-  // bank conflicts.  Only the rows that exist are loaded: the others only feed output rows that are never stored.
-  const int n_dma = (M + 3) / 4;
+  // bank conflicts.  Rows past M re-read the last row: they only feed output rows that are never stored.
   const int dma_row = lane >> 4, dma_slot = lane & 15;
-  auto dma_a = [&](int g, int stage) {
-    g = g < g_end ? g : g_end - 1;
-    bf16 *dst = (stage ? St1 : St0) + wave_u * (32 * GROUP);
+  auto dma_a = [&](int g, int st) {
+    g = g < g_end ? g : g_end - 1;                       // past the range: a valid group, not used
+    bf16 *dst = stage(st);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (j < n_dma) {
-        const int r = 4 * j + dma_row;
-        const bf16 *src = A + (size_t)(r < M ? r : M - 1) * K + (size_t)g * GROUP + ((dma_slot ^ (r & 15)) << 3);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(dst + j * 512), 16, 0, 0);
-      }
+    for (int j = 0; j < MR / 4; ++j) {
+      const int r = 4 * j + dma_row;
+      const bf16 *src = A + (size_t)(r < M ? r : M - 1) * K + (size_t)g * GROUP + ((dma_slot ^ (r & 15)) << 3);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(dst + j * 512), 16, 0, 0);
     }
   };
-  // fragment of MFMA step i: this lane's row, chunk 8 half + i
-  const int frag_off = col * GROUP;
-  auto frag_a = [&](int stage, int i) {
-    const bf16 *reg = (stage ? St1 : St0) + wave_u * (32 * GROUP);
-    return *(const bf16x8 *)&reg[frag_off + (((half * 8 + i) ^ (col & 15)) << 3)];
+  // Fragments of the eight MFMA steps of a group: this lane's row (rows past the tile repeat it), chunks 8 half + i.
+  // They are read by inline assembly with its own wait: for LDS reads that it can see, the compiler makes the wave
+  // wait for every load in flight whenever it cannot tell their stage from the one a direct-to-LDS load is filling
+  // (here: in two of four groups), which puts a round trip to memory into each of those groups.
+  const int frag_row = col & (MR - 1);
+  unsigned frag_off[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) frag_off[i] = (unsigned)(frag_row * GROUP + (((half * 8 + i) ^ (frag_row & 15)) << 3)) * 2u;
+  auto read_frags = [&](int st, bf16x8 (&fa)[8]) {
+    const unsigned base = (unsigned)(uintptr_t)LDS_PTR(stage(st));
+    asm volatile(
+        "ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
+        "ds_read_b128 %4, %12\n\tds_read_b128 %5, %13\n\tds_read_b128 %6, %14\n\tds_read_b128 %7, %15\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(fa[0]), "=&v"(fa[1]), "=&v"(fa[2]), "=&v"(fa[3]), "=&v"(fa[4]), "=&v"(fa[5]), "=&v"(fa[6]), "=&v"(fa[7])
+        : "v"(base + frag_off[0]), "v"(base + frag_off[1]), "v"(base + frag_off[2]), "v"(base + frag_off[3]),
+          "v"(base + frag_off[4]), "v"(base + frag_off[5]), "v"(base + frag_off[6]), "v"(base + frag_off[7])
+        : "memory");
   };
 
-  f32x16 acc[2], tmp[2];
+  f32x16 acc[2], tmp[2], asum;                         // asum: the activations' own sum over the group, per output row
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[j][r] = tmp[j][r] = 0.f;
+  for (int r = 0; r < 16; ++r) acc[0][r] = acc[1][r] = tmp[0][r] = tmp[1][r] = asum[r] = 0.f;
 
-  // the packed weights of a group and, with them, their scales: loads complete in order, so a scale fetched when it
-  // is needed would make the wave wait for everything requested before it
-  struct Fetched { u32x4 w[2][2]; bf16 s[2]; };
+  // The packed weights of a group and, with them, their scales (loads complete in order, so a scale fetched when
+  // it is needed would make the wave wait for everything requested before it).  Requested by inline assembly: the
+  // compiler then keeps no account of them, and the one counted wait in front of a group is the only wait there
+  // is; for loads that it issues itself it falls back to waiting for all of them wherever it loses count (across
+  // the loop's back edge: once per turn).  A set is read only behind the counted wait that covers it.
+  struct Fetched { u32x4 w[2][2]; unsigned s[2]; };
   auto load_w = [&](int g, Fetched &f) {
-    g = g < g_end ? g : g_end - 1;                       // past the range: a valid group, not used
+    g = g < g_end ? g : g_end - 1;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      f.w[j][0] = *(const u32x4 *)(bq[j] + (size_t)g * 16);
-      f.w[j][1] = *(const u32x4 *)(bq[j] + (size_t)g * 16 + 4);
-      f.s[j] = sc[j][g];
+      const uint32_t *src = bq[j] + (size_t)g * 16;
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(f.w[j][0]) : "v"(src) : "memory");
+      asm volatile("global_load_dwordx4 %0, %1, off offset:16" : "=&v"(f.w[j][1]) : "v"(src) : "memory");
+      asm volatile("global_load_ushort %0, %1, off" : "=&v"(f.s[j]) : "v"(sc[j] + g) : "memory");
     }
   };
-  // The weights of kAhead groups are in flight while one is multiplied (a ring of kAhead + 1 register sets, the
-  // loop unrolled over it so that every set has a fixed place); activations one group ahead.
-  constexpr int NW = kSkinnyAhead + 1;
-  static_assert(NW % 2 == 0, "the activation sets alternate inside the unrolled ring");
-  const int g_first = g_begin + wave;
+
+  // The n-th group of a wave uses weight set n % NW and stage n % NS; the loop is unrolled over NW groups so that
+  // both are fixed per position.  In front of group n the wave requests the tile of group n + NS - 1 and then the
+  // weights of group n + NW - 1 (6 loads); the prologue issues the same requests in the same order.
+  const int g_first = g_begin + wave_u;
   if (g_first < g_end) {
     Fetched f[NW];
-    dma_a(g_first, 0);
 #pragma unroll
-    for (int d = 0; d < NW - 1; ++d) load_w(g_first + 4 * d, f[d]);
+    for (int d = 0; d < NW - NS; ++d) load_w(g_first + 4 * d, f[d]);
+#pragma unroll
+    for (int k = 0; k < NS - 1; ++k) {
+      asm volatile("" ::: "memory");       // the compiler keeps the order of the requests: the counted wait relies on it
+      dma_a(g_first + 4 * k, k);
+      asm volatile("" ::: "memory");
+      load_w(g_first + 4 * (NW - NS + k), f[NW - NS + k]);
+    }
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (bf16)1.0f;
     for (int base = g_first; base < g_end; base += 4 * NW) {
 #pragma unroll
       for (int u = 0; u < NW; ++u) {
         const int gg = base + 4 * u;
         if (gg >= g_end) break;
-        // The activation tile of this group was requested before the latest set of weights (4 + 2 loads): once
-        // at most those are outstanding it has landed (loads complete in order; the wave reads only its own tile,
-        // so no barrier is needed).
-        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        dma_a(gg + 4, (u + 1) & 1);          // first: needed earlier than the weights requested below
+        // What this group reads must have landed: its tile, requested NS - 1 groups ago, and its weights, requested
+        // NW - 1 groups ago, i.e. earlier than the tile (NW > NS) or right behind it (NW == NS).  Every group since
+        // has requested MR / 4 + 6 loads, and loads complete in order, so: at most 6 outstanding (the weights that
+        // followed the tile, NW > NS = 2), or at most (NS - 2) (MR / 4 + 6) = 20 (NW == NS = 4).  The wave reads
+        // only its own tile, so no barrier is needed.
+        static_assert((NS == 2 && NW > NS) || (NS == 4 && NW == NS && (NS - 2) * (MR / 4 + 6) == 20), "the counted waits below");
+        if (NS == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+        dma_a(gg + 4 * (NS - 1), (u + NS - 1) % NS);
+        asm volatile("" ::: "memory");
         load_w(gg + 4 * (NW - 1), f[(u + NW - 1) % NW]);
+        asm volatile("" ::: "memory");
         const Fetched &cur = f[u];
-        const float s0 = (float)cur.s[0] * 0.0625f, s1 = (float)cur.s[1] * 0.0625f;     // the weights come as 16 q
+        const float s0 = __uint_as_float(cur.s[0] << 16), s1 = __uint_as_float(cur.s[1] << 16);     // bf16 -> fp32
+        bf16x8 frags[8];
+        read_frags(u % NS, frags);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const bf16x8 fa = frag_a(u & 1, i);
-          tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_x16(cur.w[0][i >> 2][i & 3]), tmp[0], 0, 0, 0);
-          tmp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_x16(cur.w[1][i >> 2][i & 3]), tmp[1], 0, 0, 0);
+          const bf16x8 fa = interleave_halves(frags[i]);
+          tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_plus24(cur.w[0][i >> 2][i & 3]), tmp[0], 0, 0, 0);
+          tmp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_plus24(cur.w[1][i >> 2][i & 3]), tmp[1], 0, 0, 0);
+          asum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, ones, asum, 0, 0, 0);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          acc[0][r] = fmaf(tmp[0][r], s0, acc[0][r]);
-          acc[1][r] = fmaf(tmp[1][r], s1, acc[1][r]);
+          acc[0][r] = fmaf(fmaf(-24.f, asum[r], tmp[0][r]), s0, acc[0][r]);
+          acc[1][r] = fmaf(fmaf(-24.f, asum[r], tmp[1][r]), s1, acc[1][r]);
           tmp[0][r] = 0.f;
           tmp[1][r] = 0.f;
+          asum[r] = 0.f;
         }
       }
     }
   }
 
-  __syncthreads();                                       // every wave is done with its stage reads
-  float (*part)[2][16][64] = (float (*)[2][16][64])St0;
+  __syncthreads();                                       // every wave is done with its stage reads (and loads)
+  // partial results of wave w: 8 KB each, four of them in the first array (32-row tiles) or two per array
+  auto part = [&](int w) -> float * {
+    return MR == 32 ? (float *)St0 + w * 2048 : (float *)(w < 2 ? St0 : St1) + (w & 1) * 2048;
+  };
+  {
+    float *mine = part(wave_u);
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) part[wave][j][r][lane] = acc[j][r];
+      for (int r = 0; r < 16; ++r) mine[(j * 16 + r) * 64 + lane] = acc[j][r];
+  }
   __syncthreads();
   // D layout of the 32x32 MFMA: lane holds column lane%32 (a weight row) and rows (tokens) 8*(r/4) + 4*(lane/32) + r%4.
 #pragma unroll
@@ -386,7 +436,10 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
     const int m = 8 * (r >> 2) + 4 * (L >> 5) + (r & 3), c = L & 31;
     float v[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) v[j] = (part[0][j][r][L] + part[1][j][r][L]) + (part[2][j][r][L] + part[3][j][r][L]);
+    for (int j = 0; j < 2; ++j) {
+      const int at = (j * 16 + r) * 64 + L;
+      v[j] = (part(0)[at] + part(1)[at]) + (part(2)[at] + part(3)[at]);
+    }
     if (m >= M) continue;
     if (EPI == ARB_EPI_SWIGLU_BF16) {
       ((bf16 *)Cv)[(size_t)m * N + tile * 32 + c] = (bf16)(v[0] * __builtin_amdgcn_rcpf(1.0f + __expf(-v[0])) * v[1]);
@@ -434,7 +487,10 @@ arb_status launch_gemm_w4(const bf16 *A, const uint32_t *Bq, const bf16 *Bscale,
   const dim3 grid(skinny ? (epilogue == ARB_EPI_SWIGLU_BF16 ? N / 32 : N / 64) : tiles_m * tiles_n, splits), block(256);
 #define ARB_W4(E)                                                                                                    \
   do {                                                                                                               \
-    if (skinny) hipLaunchKernelGGL((gemm_w4_skinny_kernel<E>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K);       \
+    if (skinny && M <= 16)                                                                                           \
+      hipLaunchKernelGGL((gemm_w4_skinny_kernel<E, 16, 4>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K);          \
+    else if (skinny)                                                                                                 \
+      hipLaunchKernelGGL((gemm_w4_skinny_kernel<E, 32, 2>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K);          \
     else hipLaunchKernelGGL((gemm_w4_kernel<E>), grid, block, 0, st, A, Bq, Bscale, C, M, N, K, tiles_m, tiles_n);   \
   } while (0)
   switch (epilogue) {
