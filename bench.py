@@ -284,6 +284,46 @@ def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4):
             "roles": "draft 1.5B shape, target 8B shape, router 1.5B shape + linear head; random-init, bf16"}
 
 
+def run_w4_few_tokens(rows=16, reps=12):
+    """The quantized-draft projections at a handful of tokens (Section 5.1's weight-quantized drafts, drafting token
+    by token): each 4-bit projection of the 8B and 1.5B shapes at `rows` activation rows, beside the bf16 kernel on
+    the same shape; microseconds per launch by HIP events over launches that rotate through four copies of the
+    weights (so that they come from memory), and the packed-weight bytes per second that is."""
+    import torch
+
+    import paper_2512_05033_amd as A
+
+    g = torch.Generator(device="cuda").manual_seed(7)
+
+    def per_launch_us(fn):
+        for i in range(4):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    out = []
+    for label, n, k, epi in [("8B gate/up", 14336, 4096, A.ARB_EPI_SWIGLU_BF16), ("8B down", 4096, 14336, A.ARB_EPI_STORE_F32),
+                             ("8B QKV", 6144, 4096, A.ARB_EPI_STORE_BF16), ("1.5B gate/up", 8960, 1536, A.ARB_EPI_SWIGLU_BF16),
+                             ("1.5B down", 1536, 8960, A.ARB_EPI_STORE_F32)]:
+        w_rows = 2 * n if epi == A.ARB_EPI_SWIGLU_BF16 else n
+        dense = [(torch.randn(w_rows, k, device="cuda", generator=g) * 0.05).bfloat16() for _ in range(4)]
+        packed = [A.arb_w4_quantize(w) for w in dense]
+        x = torch.randn(rows, k, device="cuda", generator=g).bfloat16()
+        us4 = per_launch_us(lambda i: A.arb_stage_gemm_w4(x, *packed[i % 4], epi))
+        us16 = per_launch_us(lambda i: A.arb_stage_gemm(x, dense[i % 4], epi))
+        out.append({"projection": label, "rows": rows, "weight_rows": w_rows, "K": k, "w4_us": round(us4, 2),
+                    "bf16_us": round(us16, 2), "packed_weight_TBps": round(w_rows * k / 2 / us4 / 1e6, 3)})
+        del dense, packed
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +336,7 @@ def main():
     ap.add_argument("--stage-reps", type=int, default=3, help="extra passes per stage for the per-stage times (0: none, "
                     "for hardware-counter runs; per_config then holds the step times only)")
     ap.add_argument("--alg1", type=int, default=1, help="1: also time Algorithm 1 end to end on three synthetic roles (field alg1)")
+    ap.add_argument("--w4", type=int, default=1, help="1: also time the 4-bit projections at 16 rows beside the bf16 ones (field w4_few_tokens)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the warm-up, run one plain device copy of this many MiB (a kernel of known traffic "
                          "that hardware-counter runs are scaled by)")
@@ -345,6 +386,9 @@ def main():
     if args.alg1 and args.stage_reps > 0:
         out["alg1"] = run_alg1()
         print(f"bench: Algorithm 1 done: {out['alg1']['steps_per_s']:.1f} steps per second", file=sys.stderr, flush=True)
+    if args.w4 and args.stage_reps > 0:
+        out["w4_few_tokens"] = run_w4_few_tokens()
+        print("bench: 4-bit projections at 16 rows done", file=sys.stderr, flush=True)
     print(json.dumps(out))
 
 
