@@ -47,12 +47,18 @@ __device__ __forceinline__ bf16x8 expand_nibbles(uint32_t w) {
 // fp32: sum_k a_k (24 + q_k) - 24 sum_k a_k, with the second sum from an MFMA against ones; the terms are about
 // five times the size of the result, so fp32 loses two or three more bits than without the detour, far below
 // what the rounding of the output, or an fp32 test bar of 1e-5, sees.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t bits) {      // (x & mask) | bits, one instruction
+  uint32_t d;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(bits));
+  return d;
+}
 __device__ __forceinline__ bf16x8 expand_nibbles_plus24(uint32_t w) {
+  const uint32_t mask = 0x00780078u, bits = 0x41804180u;
   u32x4 d;
-  d[0] = ((w << 3) & 0x00780078u) | 0x41804180u;
-  d[1] = ((w >> 1) & 0x00780078u) | 0x41804180u;
-  d[2] = ((w >> 5) & 0x00780078u) | 0x41804180u;
-  d[3] = ((w >> 9) & 0x00780078u) | 0x41804180u;
+  d[0] = and_or(w << 3, mask, bits);
+  d[1] = and_or(w >> 1, mask, bits);
+  d[2] = and_or(w >> 5, mask, bits);
+  d[3] = and_or(w >> 9, mask, bits);
   return __builtin_bit_cast(bf16x8, d);
 }
 // elements 0..7 -> 0, 4, 1, 5, 2, 6, 3, 7
