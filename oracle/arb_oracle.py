@@ -405,20 +405,24 @@ def arbitrage_inference(question, draft_step, router_score, target_step, tau: fl
 W4_GROUP = 128
 
 
-def w4_quantize(w_bits: np.ndarray):
-    """Group-wise symmetric 4-bit quantization of a bf16 weight matrix [N, K] (bit patterns):
-    per row and group of 128 consecutive k, scale = bf16(max|w| / 7) and
-    q = clip(rint(w / scale), -8, 7) (0 where the scale is 0), quotients in fp32,
+def w4_quantize(w_bits: np.ndarray, bits: int = 4):
+    """Group-wise symmetric quantization of a bf16 weight matrix [N, K] (bit patterns) to `bits`-bit
+    integers (4: the Q4 self-drafts of Section 5.1; 3: the 3-bit Qwen draft of Section 5.2): with
+    qmax = 2^(bits-1) - 1, per row and group of 128 consecutive k, scale = bf16(max|w| / qmax) and
+    q = clip(rint(w / scale), -qmax - 1, qmax) (0 where the scale is 0), quotients in fp32,
     round-half-even.  Returns (q int8 [N, K], scale bits uint16 [N, K/128]).  (The paper
     quantizes its drafts with GPTQ / llama.cpp; how the integers are chosen offline does
     not matter to the forward, which only sees integers and group scales.)"""
+    if bits not in (3, 4):
+        raise ValueError("bits")
+    qmax = 2 ** (bits - 1) - 1
     w = bf16_to_float(w_bits).astype(np.float32)
     N, K = w.shape
     g = w.reshape(N, K // W4_GROUP, W4_GROUP)
-    scale_bits = float_to_bf16(np.abs(g).max(axis=2) / np.float32(7.0))
+    scale_bits = float_to_bf16(np.abs(g).max(axis=2) / np.float32(qmax))
     scale = bf16_to_float(scale_bits).astype(np.float32)
     safe = np.where(scale == 0, np.float32(1.0), scale)[:, :, None]
-    q = np.clip(np.rint(g / safe), -8, 7)
+    q = np.clip(np.rint(g / safe), -qmax - 1, qmax)
     q = np.where(scale[:, :, None] == 0, 0, q).astype(np.int8)
     return q.reshape(N, K), scale_bits
 
@@ -431,7 +435,8 @@ def w4_dequantize(q: np.ndarray, scale_bits: np.ndarray) -> np.ndarray:
 
 def w4_pack(q: np.ndarray) -> np.ndarray:
     """Storage format: offset-binary nibbles (q + 8), eight consecutive k per uint32,
-    k ascending from the least significant nibble.  [N, K] -> uint32 [N, K/8]."""
+    k ascending from the least significant nibble (3-bit integers use the same nibbles).
+    [N, K] -> uint32 [N, K/8]."""
     N, K = q.shape
     u = (q.astype(np.int32) + 8).astype(np.uint32).reshape(N, K // 8, 8)
     return (u << (4 * np.arange(8, dtype=np.uint32))[None, None, :]).sum(axis=2, dtype=np.uint64).astype(np.uint32)

@@ -655,6 +655,31 @@ def test_w4_quantization_definition():
         assert (int(p[n, k // 8]) >> (4 * (k % 8))) & 15 == int(q[n, k]) + 8
 
 
+def test_w3_quantization_is_the_same_rule_with_levels_minus4_to_3():
+    r = np.random.default_rng(13)
+    w = O.float_to_bf16(r.normal(0, 0.02, (5, 256)))
+    w[1, :128] = 0
+    q, sb = O.w4_quantize(w, bits=3)
+    wf, s = O.bf16_to_float(w), O.bf16_to_float(sb)
+    g = lambda a: a.reshape(5, 2, 128)
+    assert q.dtype == np.int8 and q.min() >= -4 and q.max() <= 3 and np.all(q[1, :128] == 0) and s[1, 0] == 0
+    assert np.allclose(s, np.abs(g(wf)).max(2) / 3, rtol=2 ** -8)
+    wd = O.w4_dequantize(q, sb)
+    unclipped = np.abs(g(wf)) <= 3 * s[:, :, None]
+    assert np.all(np.abs(g(wd) - g(wf))[unclipped] <= 0.5 * np.repeat(s[:, :, None], 128, 2)[unclipped] * (1 + 1e-6))
+    big = np.abs(g(q)).max(2)
+    assert np.all((big[s > 0] == 3) | (big[s > 0] == 4))
+    # eight levels are coarser than sixteen: on the same weights the 3-bit error is the larger one (about 7/3 of it)
+    q4, sb4 = O.w4_quantize(w)
+    e3 = np.sqrt(np.mean((wd - wf) ** 2)); e4 = np.sqrt(np.mean((O.w4_dequantize(q4, sb4) - wf) ** 2))
+    assert 1.8 < e3 / e4 < 2.9
+    # the nibble format holds them unchanged
+    p = O.w4_pack(q)
+    assert (int(p[4, 31]) >> 28) & 15 == int(q[4, 255]) + 8
+    with pytest.raises(ValueError):
+        O.w4_quantize(w, bits=5)
+
+
 # ----------------------------------------------------------------------- stored values
 
 def _golden(name):
