@@ -287,6 +287,12 @@ arb_status arb_pack_k_blocked(const void *W, int64_t rows, int32_t K, void *pack
  * scales device bf16 [N, K/128]. */
 arb_status arb_w4_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream);
 
+/* The same with 3-bit integers (the 3-bit self-draft of Section 5.2): scale = bf16(max|w| / 3),
+ * q = clip(rint(w / scale), -4, 3), stored in the same nibbles (q + 8), so that everything that takes the
+ * 4-bit format takes these weights unchanged (they occupy 4 bits each; a denser packing is not offered).
+ * Arguments, shapes and errors as arb_w4_quantize. */
+arb_status arb_w3_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream);
+
 /* arb_stage_gemm with such weights: C = A W'^T, W'[n,k] = q[n,k] * scale[n, k/128] (no rounding of the
  * products; fp32 accumulation).  K % 128 == 0; N and epilogues as arb_stage_gemm. */
 arb_status arb_stage_gemm_w4(const void *A, const void *packed, const void *scales, void *C, int32_t M, int32_t N,

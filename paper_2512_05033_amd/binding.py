@@ -28,7 +28,7 @@ _STATUS = {0: "ARB_OK", 1: "ARB_EINVAL", 2: "ARB_ESHAPE", 3: "ARB_ECAPACITY", 4:
 NOALLOC_SCRATCH_BYTES = 64 << 20      # ARB_NOALLOC_SCRATCH_BYTES of include/arb.h
 
 EXPORTS = ["arb_model_create", "arb_model_destroy", "arb_workspace_bytes", "arb_score_steps", "arb_score_steps_noalloc", "arb_prefill",
-           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_step_advance", "arb_pack_steps", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_pack_k_blocked", "arb_w4_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
+           "arb_route", "arb_next_token", "arb_next_token_workspace_bytes", "arb_first_stop", "arb_step_advance", "arb_pack_steps", "arb_advantage_route", "arb_budget_threshold", "arb_slot_mapping", "arb_stage_gemm", "arb_pack_k_blocked", "arb_w4_quantize", "arb_w3_quantize", "arb_stage_gemm_w4", "arb_stage_attention", "arb_stage_rmsnorm",
            "arb_stage_rope_append", "arb_stage_norm_pool_head", "arb_stage_layers", "arb_gemm_large_tile_columns", "arb_model_trace", "arb_model_trace_count",
            "arb_last_error"]
 
@@ -102,6 +102,7 @@ def load_library(path: Optional[str] = None):
     lib.arb_stage_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_int32, C.c_void_p]
     lib.arb_w4_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.arb_w3_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.arb_pack_k_blocked.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     lib.arb_stage_gemm_w4.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                       C.c_int32, C.c_void_p]
@@ -415,16 +416,25 @@ def arb_pack_k_blocked(w: torch.Tensor, stream=None) -> torch.Tensor:
     return packed
 
 
-def arb_w4_quantize(w: torch.Tensor, stream=None):
-    """bf16 [N, K] -> (packed int32 [N, K/8] (the uint32 words), scales bf16 [N, K/128])."""
+def _quantize(entry, w: torch.Tensor, stream):
     _dev(w, torch.bfloat16)
     N, K = w.shape
     if K % 128:
         raise ValueError("K must be a multiple of 128")
     packed = torch.empty(N, K // 8, dtype=torch.int32, device=w.device)
     scales = torch.empty(N, K // 128, dtype=torch.bfloat16, device=w.device)
-    _check(load_library().arb_w4_quantize(_ptr(w), N, K, _ptr(packed), _ptr(scales), _stream(stream)))
+    _check(getattr(load_library(), entry)(_ptr(w), N, K, _ptr(packed), _ptr(scales), _stream(stream)))
     return packed, scales
+
+
+def arb_w4_quantize(w: torch.Tensor, stream=None):
+    """bf16 [N, K] -> (packed int32 [N, K/8] (the uint32 words), scales bf16 [N, K/128])."""
+    return _quantize("arb_w4_quantize", w, stream)
+
+
+def arb_w3_quantize(w: torch.Tensor, stream=None):
+    """The same with 3-bit integers (-4..3) in the same nibble format."""
+    return _quantize("arb_w3_quantize", w, stream)
 
 
 def arb_stage_gemm_w4(a: torch.Tensor, packed: torch.Tensor, scales: torch.Tensor, epilogue: int = ARB_EPI_STORE_BF16,
@@ -448,12 +458,13 @@ def arb_stage_gemm_w4(a: torch.Tensor, packed: torch.Tensor, scales: torch.Tenso
 
 
 class QuantizedWeights:
-    """The weights of a model with its four projection matrices per layer in the 4-bit format."""
+    """The weights of a model with its four projection matrices per layer in the 4-bit format (bits = 3: 3-bit integers in it)."""
 
-    def __init__(self, w):
+    def __init__(self, w, bits: int = 4):
         self.embed, self.g_attn, self.g_mlp, self.g_final = w.embed, w.g_attn, w.g_mlp, w.g_final
         self.w_head, self.b_head = w.w_head, w.b_head
-        pairs = [[arb_w4_quantize(t) for t in l] for l in (w.wqkv, w.wo, w.wgu, w.wd)]
+        quantize = {4: arb_w4_quantize, 3: arb_w3_quantize}[bits]
+        pairs = [[quantize(t) for t in l] for l in (w.wqkv, w.wo, w.wgu, w.wd)]
         self.wqkv, self.wo, self.wgu, self.wd = ([p for p, _ in l] for l in pairs)
         self.scales = [[s for _, s in l] for l in pairs]
 

@@ -548,7 +548,13 @@ extern "C" arb_status arb_pack_k_blocked(const void *W, int64_t rows, int32_t K,
 extern "C" arb_status arb_w4_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream) {
   if (N == 0) return ARB_OK;
   if (!W || !packed || !scales) return arb_fail(ARB_EINVAL, "arb_w4_quantize: null pointer");
-  return launch_w4_quantize((const bf16 *)W, N, K, (uint32_t *)packed, (bf16 *)scales, (hipStream_t)stream);
+  return launch_w4_quantize((const bf16 *)W, N, K, (uint32_t *)packed, (bf16 *)scales, 4, (hipStream_t)stream);
+}
+
+extern "C" arb_status arb_w3_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream) {
+  if (N == 0) return ARB_OK;
+  if (!W || !packed || !scales) return arb_fail(ARB_EINVAL, "arb_w3_quantize: null pointer");
+  return launch_w4_quantize((const bf16 *)W, N, K, (uint32_t *)packed, (bf16 *)scales, 3, (hipStream_t)stream);
 }
 
 extern "C" arb_status arb_stage_gemm_w4(const void *A, const void *packed, const void *scales, void *C, int32_t M,

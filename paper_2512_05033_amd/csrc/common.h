@@ -139,6 +139,6 @@ arb_status launch_pack_steps(const int32_t *steps, int S, const int32_t *rows, c
                              hipStream_t st);
 
 // gemm_w4.hip: 4-bit weights (offset-binary nibbles, eight k per uint32, bf16 scale per row and 128 k)
-arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, hipStream_t st);
+arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, int bits, hipStream_t st);
 arb_status launch_gemm_w4(const bf16 *A, const uint32_t *Bq, const bf16 *Bscale, void *C, int M, int N, int K,
                           int epilogue, hipStream_t st, int splits = 1);

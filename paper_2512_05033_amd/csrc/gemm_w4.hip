@@ -72,6 +72,8 @@ __device__ __forceinline__ bf16x8 interleave_halves(bf16x8 a) {
   return __builtin_bit_cast(bf16x8, d);
 }
 
+// QMAX = 7: 4-bit integers -8..7; QMAX = 3: 3-bit integers -4..3 (same nibble storage)
+template <int QMAX>
 __global__ __launch_bounds__(256) void w4_quantize_kernel(const bf16 *__restrict__ W, int N, int K,
                                                           uint32_t *__restrict__ packed, bf16 *__restrict__ scales) {
   // 16 threads per group of 128 weights, 8 weights (one word) each
@@ -86,13 +88,13 @@ __global__ __launch_bounds__(256) void w4_quantize_kernel(const bf16 *__restrict
   for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf((float)w[e]));
 #pragma unroll
   for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 16));
-  const bf16 scale = (bf16)(m / 7.0f);
+  const bf16 scale = (bf16)(m / (float)QMAX);
   const float sf = (float)scale;
   uint32_t word = 0;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     float q = sf == 0.f ? 0.f : rintf((float)w[e] / sf);
-    q = fminf(fmaxf(q, -8.f), 7.f);
+    q = fminf(fmaxf(q, -(float)(QMAX + 1)), (float)QMAX);
     word |= (uint32_t)((int)q + 8) << (4 * e);
   }
   packed[(size_t)n * (K / 8) + g * 16 + l16] = word;
@@ -463,11 +465,14 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
 
 }  // namespace
 
-arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, hipStream_t st) {
+arb_status launch_w4_quantize(const bf16 *W, int N, int K, uint32_t *packed, bf16 *scales, int bits, hipStream_t st) {
   if (N == 0) return ARB_OK;
+  if (bits != 3 && bits != 4) return arb_fail(ARB_EUNSUPPORTED, "weight quantization to %d bits (3 or 4)", bits);
   if (N < 0 || K <= 0 || K % GROUP != 0) return arb_fail(ARB_EUNSUPPORTED, "w4_quantize: N=%d, K=%d (K must be a multiple of %d)", N, K, GROUP);
   const long long groups = (long long)N * (K / GROUP);
-  hipLaunchKernelGGL(w4_quantize_kernel, dim3((unsigned)((groups + 15) / 16)), dim3(256), 0, st, W, N, K, packed, scales);
+  const dim3 grid((unsigned)((groups + 15) / 16)), block(256);
+  if (bits == 4) hipLaunchKernelGGL(w4_quantize_kernel<7>, grid, block, 0, st, W, N, K, packed, scales);
+  else hipLaunchKernelGGL(w4_quantize_kernel<3>, grid, block, 0, st, W, N, K, packed, scales);
   ARB_CHECK_LAUNCH("w4_quantize");
   return ARB_OK;
 }

@@ -702,15 +702,29 @@ def _packed_np(t):
     return t.cpu().numpy().view(np.uint32)
 
 
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("N,K", [(128, 128), (300, 1536), (2048, 8960)])
-def test_w4_quantize_bit_exact(A, N, K):
+def test_w4_quantize_bit_exact(A, N, K, bits):
     w = rand_bf16((N, K), 0.02, 51)
     w[1, :128] = 0                                                          # a group of zeros
     w[2, 5] = 3.0                                                           # an outlier that sets its group's scale
-    packed, scales = A.arb_w4_quantize(w)
-    q, sb = O.w4_quantize(W.bf16_bits(w))
+    packed, scales = (A.arb_w4_quantize if bits == 4 else A.arb_w3_quantize)(w)
+    q, sb = O.w4_quantize(W.bf16_bits(w), bits)
     assert np.array_equal(W.bf16_bits(scales), sb)
     assert np.array_equal(_packed_np(packed), O.w4_pack(q))
+
+
+@pytest.mark.parametrize("M", [9, 200])
+def test_gemm_takes_3bit_weights_in_the_nibble_format(A, M):
+    """3-bit integers travel in the 4-bit format: both kernels (few rows / tiles) against the definition."""
+    N, K = 512, 1536
+    a, w = rand_bf16((M, K), 1.0, 54), rand_bf16((N, K), 0.05, 55)
+    packed, scales = A.arb_w3_quantize(w)
+    q, sb = O.w4_quantize(W.bf16_bits(w), 3)
+    assert q.min() >= -4 and q.max() == 3
+    ref = bf16_np(a) @ O.w4_dequantize(q, sb).T
+    got = A.arb_stage_gemm_w4(a, packed, scales, A.ARB_EPI_STORE_F32).cpu().numpy()
+    assert rel_err(got, ref) < 1e-5
 
 
 @pytest.mark.parametrize("M,N,K,epi", [(1, 128, 128, "store"), (16, 1536, 8960, "f32"), (200, 2048, 1536, "store"),
@@ -741,8 +755,8 @@ def test_w4_gemm(A, M, N, K, epi):
         assert got.shape == (M, N) and rel_err(got, O.silu(ref[:, :N]) * ref[:, N:]) < 5e-3
 
 
-@pytest.mark.parametrize("few_tokens", [False, True])
-def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A, few_tokens):
+@pytest.mark.parametrize("few_tokens,bits", [(False, 4), (True, 4), (True, 3)])
+def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A, few_tokens, bits):
     """The whole forward with 4-bit projection weights (C2's shape, 2 layers, so that split-K, SwiGLU
     and the plain epilogue all run on packed weights) against the oracle given the dequantized values."""
     w = W.scaled(W.C2, n_layers=2, batch=4)
@@ -750,7 +764,7 @@ def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A, fe
         w = replace(w, step=("fixed", 5, 5))
     batch = W.make_batch(w)
     weights = W.make_weights(w.model, w.seed, "cuda", gain_jitter=0.1)
-    qw = A.QuantizedWeights(weights)
+    qw = A.QuantizedWeights(weights, bits)
     model = H().make_model(w.model, qw)
     ks, vs = W.make_kv_pools(w, batch, "cuda")
     kv, db = A.KVCache(ks, vs), H().device_batch(batch)
@@ -758,7 +772,7 @@ def test_quantized_draft_forward_matches_the_oracle_on_dequantized_weights(A, fe
     # the oracle's parameters: every projection replaced by its dequantized values (float64 arrays)
     p = oracle_params(W.make_weights(w.model, w.seed, "cpu", gain_jitter=0.1))
     for name in ("wqkv", "wo", "wgu", "wd"):
-        setattr(p, name, [O.w4_dequantize(*O.w4_quantize(bits)) for bits in getattr(p, name)])
+        setattr(p, name, [O.w4_dequantize(*O.w4_quantize(wb, bits)) for wb in getattr(p, name)])
     kp, vp = oracle_pools(*W.make_kv_pools(w, batch, "cpu"))
     s_ref, e_ref, y_ref = O.score_steps(oracle_model(w.model), p, kp, vp, batch.token_ids, batch.prefix_lens,
                                         batch.cu_step_lens, batch.block_tables, batch.tau)
