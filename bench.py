@@ -221,8 +221,9 @@ def run_config(name, steps, warmup, cpu_layers, copy_probe_mib=0, stage_reps=3):
     return entry
 
 
-def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4):
-    """Algorithm 1 end to end on three synthetic roles (draft: 1.5B shape, target: 8B shape, router: 1.5B shape with
+def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4, quantized_draft=False):
+    """Algorithm 1 end to end on three synthetic roles (draft: 1.5B shape, or with quantized_draft the 8B shape with
+    4-bit projection weights, the Q4-8B/8B/1.5B regime of Section 5.3; target: 8B shape; router: 1.5B shape with
     the linear head; random-init weights, a common vocabulary): reasoning steps per second of the whole loop
     (draft step token by token, router score, target step for the escalated sequences).  The separator is a
     token the random draft really emits and the threshold the median of a probe pass's scores, so steps end
@@ -242,9 +243,11 @@ def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4):
     n_blocks = n_questions * blocks_per_seq
     tables = np.random.default_rng(5).permutation(n_blocks).astype(np.int32).reshape(n_questions, blocks_per_seq)
 
-    def role(name, shape, seed, lm):
+    def role(name, shape, seed, lm, four_bit=False):
         m = replace(shape, vocab=vocab)
         weights = W.make_weights(m, seed, "cuda")
+        if four_bit:
+            weights = A.QuantizedWeights(weights)
         model = harness.make_model(m, weights, has_router_head=not lm)
         dims = (n_blocks, m.n_kv_heads, m.kv_block, m.head_dim)
         kv = A.KVCache([torch.zeros(dims, dtype=torch.bfloat16, device="cuda") for _ in range(m.n_layers)],
@@ -252,8 +255,8 @@ def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4):
         w_lm = W.normal_bf16(seed, "lm_head", (m.vocab, m.d_model), 0.02, "cuda") if lm else None
         return Role(name, model, kv, w_lm)
 
-    roles = {"draft": role("draft", W.C2.model, 11, True), "target": role("target", W.C3.model, 12, True),
-             "router": role("router", W.C2.model, 13, False)}
+    draft = role("draft", W.C3.model, 11, True, four_bit=True) if quantized_draft else role("draft", W.C2.model, 11, True)
+    roles = {"draft": draft, "target": role("target", W.C3.model, 12, True), "router": role("router", W.C2.model, 13, False)}
     questions = [[int(t) for t in W.uniform_ints(21, f"q{b}", prompt, vocab).numpy()] for b in range(n_questions)]
 
     def run(tau, sep, steps):
@@ -281,7 +284,8 @@ def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4):
     return {"steps_per_s": n_steps / dt, "generated_tokens_per_s": gen / dt, "seconds": dt, "questions": n_questions,
             "prompt_tokens": prompt, "max_step_tokens": max_step_tokens, "alg1_steps": n_steps, "escalated": int(n_esc),
             "generated_tokens": gen, "mean_step_tokens": gen / max(1, sum(1 for e in trace if e[0] == "step")),
-            "roles": "draft 1.5B shape, target 8B shape, router 1.5B shape + linear head; random-init, bf16"}
+            "roles": ("draft 8B shape with 4-bit projection weights" if quantized_draft else "draft 1.5B shape") +
+                     ", target 8B shape, router 1.5B shape + linear head; random-init, bf16"}
 
 
 def run_w4_few_tokens(rows=16, reps=12):
@@ -386,6 +390,10 @@ def main():
     if args.alg1 and args.stage_reps > 0:
         out["alg1"] = run_alg1()
         print(f"bench: Algorithm 1 done: {out['alg1']['steps_per_s']:.1f} steps per second", file=sys.stderr, flush=True)
+        torch.cuda.empty_cache()
+        out["alg1_q4_draft"] = run_alg1(quantized_draft=True)
+        print(f"bench: Algorithm 1 with the 4-bit draft done: {out['alg1_q4_draft']['steps_per_s']:.1f} steps per second",
+              file=sys.stderr, flush=True)
     if args.w4 and args.stage_reps > 0:
         out["w4_few_tokens"] = run_w4_few_tokens()
         print("bench: 4-bit projections at 16 rows done", file=sys.stderr, flush=True)
