@@ -288,6 +288,55 @@ def run_alg1(n_questions=16, prompt=512, max_step_tokens=16, alg_steps=4, quanti
                      ", target 8B shape, router 1.5B shape + linear head; random-init, bf16"}
 
 
+def run_few_token_forward(reps=20):
+    """One drafting step's forward: the 1.5B shape, 16 sequences with one new token each against 2048 cached tokens
+    (what every token position of Algorithm 1's draft loop costs).  Milliseconds per forward and, by the library's
+    event hook, microseconds per layer and stage; the weights alone would take 2.62 GB / 8 TB/s = 0.33 ms."""
+    from dataclasses import replace
+
+    import torch
+
+    import harness
+    import paper_2512_05033_amd as A
+    import workloads as W
+
+    w = replace(W.C2, batch=16, step=("fixed", 1, 1), name="D1-draft1.5B-b16-p2048-s1")
+    sess = harness.setup(w, "cuda")
+    batch, model, m = sess.batch, sess.model, w.model
+    hidden = torch.empty(batch.total_tokens, m.d_model, dtype=torch.bfloat16, device="cuda")
+    scores = torch.empty(batch.batch, dtype=torch.float32, device="cuda")
+    esc = torch.empty(batch.batch, dtype=torch.uint8, device="cuda")
+
+    def step():
+        A.arb_score_steps(model, sess.kv, sess.dbatch, batch.tau, ws=sess.ws, scores=scores, escalate=esc, hidden=hidden)
+
+    for _ in range(5):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / reps * 1e3
+    ids = {"qkv": A.ARB_STAGE_QKV, "attention": A.ARB_STAGE_ATTENTION, "oproj": A.ARB_STAGE_OPROJ,
+           "gate_up": A.ARB_STAGE_GATE_UP, "down": A.ARB_STAGE_DOWN, "norm": A.ARB_STAGE_NORM,
+           "rope_append": A.ARB_STAGE_ROPE_APPEND}
+    stage_us = {}
+    for sname in STAGES:
+        t = A.StageTimer(model, ids[sname], 3 * m.n_layers)
+        t.arm()
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        dur = t.durations_ms(t.disarm())
+        t.close()
+        stage_us[sname] = round(sum(dur) / 3 / m.n_layers * 1e3, 2)
+    model.close()
+    weight_gb = m.n_layers * 2 * (m.qkv_rows * m.d_model + m.d_model * m.n_q_heads * m.head_dim + 3 * m.d_ffn * m.d_model) / 1e9
+    return {"workload": w.name, "step_tokens": batch.total_tokens, "ms_per_forward": ms, "weights_GB": round(weight_gb, 3),
+            "weights_TBps": round(weight_gb / ms, 3), "stage_us_per_layer": stage_us}
+
+
 def run_w4_few_tokens(rows=16, reps=12):
     """The quantized-draft projections at a handful of tokens (Section 5.1's weight-quantized drafts, drafting token
     by token): each 4-bit projection of the 8B and 1.5B shapes at `rows` activation rows, beside the bf16 kernel on
@@ -340,7 +389,7 @@ def main():
     ap.add_argument("--stage-reps", type=int, default=3, help="extra passes per stage for the per-stage times (0: none, "
                     "for hardware-counter runs; per_config then holds the step times only)")
     ap.add_argument("--alg1", type=int, default=1, help="1: also time Algorithm 1 end to end on three synthetic roles (field alg1)")
-    ap.add_argument("--w4", type=int, default=1, help="1: also time the 4-bit projections at 16 rows beside the bf16 ones (field w4_few_tokens)")
+    ap.add_argument("--w4", type=int, default=1, help="1: also time one few-token forward (field few_token_forward) and the 4-bit projections at 16 rows beside the bf16 ones (field w4_few_tokens)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the warm-up, run one plain device copy of this many MiB (a kernel of known traffic "
                          "that hardware-counter runs are scaled by)")
@@ -395,6 +444,8 @@ def main():
         print(f"bench: Algorithm 1 with the 4-bit draft done: {out['alg1_q4_draft']['steps_per_s']:.1f} steps per second",
               file=sys.stderr, flush=True)
     if args.w4 and args.stage_reps > 0:
+        out["few_token_forward"] = run_few_token_forward()
+        print(f"bench: few-token forward done: {out['few_token_forward']['ms_per_forward']:.3f} ms", file=sys.stderr, flush=True)
         out["w4_few_tokens"] = run_w4_few_tokens()
         print("bench: 4-bit projections at 16 rows done", file=sys.stderr, flush=True)
     print(json.dumps(out))
