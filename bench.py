@@ -339,8 +339,8 @@ def run_few_token_forward(reps=20):
 
 def run_w4_few_tokens(rows=16, reps=12):
     """The quantized-draft projections at a handful of tokens (Section 5.1's weight-quantized drafts, drafting token
-    by token): each 4-bit projection of the 8B and 1.5B shapes at `rows` activation rows, beside the bf16 kernel on
-    the same shape; microseconds per launch by HIP events over launches that rotate through four copies of the
+    by token): each 4-bit projection of the 8B and 1.5B shapes at `rows` activation rows (gate/up also at 128), beside
+    the bf16 kernel on the same shape; microseconds per launch by HIP events over launches that rotate through four copies of the
     weights (so that they come from memory), and the packed-weight bytes per second that is."""
     import torch
 
@@ -367,11 +367,12 @@ def run_w4_few_tokens(rows=16, reps=12):
         w_rows = 2 * n if epi == A.ARB_EPI_SWIGLU_BF16 else n
         dense = [(torch.randn(w_rows, k, device="cuda", generator=g) * 0.05).bfloat16() for _ in range(4)]
         packed = [A.arb_w4_quantize(w) for w in dense]
-        x = torch.randn(rows, k, device="cuda", generator=g).bfloat16()
-        us4 = per_launch_us(lambda i: A.arb_stage_gemm_w4(x, *packed[i % 4], epi))
-        us16 = per_launch_us(lambda i: A.arb_stage_gemm(x, dense[i % 4], epi))
-        out.append({"projection": label, "rows": rows, "weight_rows": w_rows, "K": k, "w4_us": round(us4, 2),
-                    "bf16_us": round(us16, 2), "packed_weight_TBps": round(w_rows * k / 2 / us4 / 1e6, 3)})
+        for m in ([rows, 128] if "gate/up" in label else [rows]):       # 128 rows: the tile kernel (one tile row)
+            x = torch.randn(m, k, device="cuda", generator=g).bfloat16()
+            us4 = per_launch_us(lambda i: A.arb_stage_gemm_w4(x, *packed[i % 4], epi))
+            us16 = per_launch_us(lambda i: A.arb_stage_gemm(x, dense[i % 4], epi))
+            out.append({"projection": label, "rows": m, "weight_rows": w_rows, "K": k, "w4_us": round(us4, 2),
+                        "bf16_us": round(us16, 2), "packed_weight_TBps": round(w_rows * k / 2 / us4 / 1e6, 3)})
         del dense, packed
         torch.cuda.empty_cache()
     return out

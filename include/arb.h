@@ -282,8 +282,10 @@ arb_status arb_pack_k_blocked(const void *W, int64_t rows, int32_t K, void *pack
 /* 4-bit weight format of the quantized draft (Section 5.1; the paper takes its integers from GPTQ /
  * llama.cpp, the forward only needs integers and group scales): per row and group of 128 consecutive
  * inputs, scale = bf16(max|w| / 7), q = clip(rint(w / scale), -8, 7) (0 where scale is 0; fp32
- * quotients, round half to even); stored as q + 8 in nibbles, eight consecutive inputs per uint32 from
- * the least significant nibble up.  W device bf16 [N, K], K % 128 == 0; packed device uint32 [N, K/8];
+ * quotients, round half to even); stored as q + 8 in nibbles, eight consecutive inputs per uint32: input
+ * 8j + 2i in nibble i and input 8j + 2i + 1 in nibble 4 + i of word j (nibble 0 = bits 0..3), i.e. the even
+ * inputs in the low half and the odd ones in the high half, two neighbours 16 bits apart, which is where a
+ * register holds a pair of bf16.  W device bf16 [N, K], K % 128 == 0; packed device uint32 [N, K/8];
  * scales device bf16 [N, K/128]. */
 arb_status arb_w4_quantize(const void *W, int32_t N, int32_t K, void *packed, void *scales, void *stream);
 

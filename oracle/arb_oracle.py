@@ -434,10 +434,13 @@ def w4_dequantize(q: np.ndarray, scale_bits: np.ndarray) -> np.ndarray:
 
 
 def w4_pack(q: np.ndarray) -> np.ndarray:
-    """Storage format: offset-binary nibbles (q + 8), eight consecutive k per uint32,
-    k ascending from the least significant nibble (3-bit integers use the same nibbles).
-    [N, K] -> uint32 [N, K/8]."""
+    """Storage format: offset-binary nibbles (q + 8), eight consecutive k per uint32: the even
+    ones in the four low nibbles, the odd ones in the four high nibbles (input 2i in nibble i,
+    input 2i + 1 in nibble 4 + i, nibble 0 the least significant), so that two neighbours sit
+    16 bits apart (3-bit integers use the same nibbles).  [N, K] -> uint32 [N, K/8]."""
     N, K = q.shape
     u = (q.astype(np.int32) + 8).astype(np.uint32).reshape(N, K // 8, 8)
-    return (u << (4 * np.arange(8, dtype=np.uint32))[None, None, :]).sum(axis=2, dtype=np.uint64).astype(np.uint32)
+    e = np.arange(8)
+    nibble = e // 2 + 4 * (e % 2)
+    return (u << (4 * nibble).astype(np.uint32)[None, None, :]).sum(axis=2, dtype=np.uint64).astype(np.uint32)
 

@@ -3,14 +3,13 @@
 // W'[n,k] = q[n,k] * scale[n, k/128], q in [-8, 7] stored as offset-binary nibbles, eight
 // consecutive k per uint32, scale bf16.
 //
-// Structure of the 128x128x64 bf16 kernel (4 waves of 64x64, double-buffered LDS, A by direct-to-LDS
-// loads), except for the weight operand: each thread fetches 16 bytes of packed weights (32 nibbles of
-// one row) one step ahead into registers, expands them to the bf16 integers -8..7 (exact) and stores
-// them into the LDS stage.  The MFMAs therefore accumulate sum_k a[m,k] q[n,k] per group of 128 k
-// (two steps) into a temporary accumulator; at the end of a group it is folded into the result with
-// one fp32 multiply by the group's scale.  No product q*scale is ever rounded to bf16, so the result
-// differs from the definition only by fp32 accumulation.  Weight traffic is a quarter of the bf16
-// kernel's, which is what the small-M (decode) case is bound by.
+// The tile kernel (more than 32 activation rows) has the geometry of the 128x128x64 bf16 kernel (4 waves of 64x64,
+// A by direct-to-LDS loads), except for the weight operand: each thread fetches 16 bytes of packed weights (32 nibbles
+// of one row) into registers, expands them to the bf16 integers -8..7 (exact) and stores them into an LDS stage.  The
+// MFMAs therefore accumulate sum_k a[m,k] q[n,k] per group of 128 k (two steps) into a temporary accumulator; at the
+// end of a group it is folded into the result with one fp32 multiply by the group's scale.  No product q*scale is ever
+// rounded to bf16, so the result differs from the definition only by fp32 accumulation.  Weight traffic is a quarter
+// of the bf16 kernel's.  Up to 32 rows a weight-streaming kernel runs instead (below).
 #include "common.h"
 
 namespace {
@@ -27,26 +26,28 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {   // element offset
   return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
-// eight nibbles (k ascending from the least significant) -> the bf16 integers nibble - 8
+// nibble of a word that holds input e of its eight: the even inputs in nibbles 0..3, the odd ones in nibbles 4..7
+__host__ __device__ constexpr int nibble_of(int e) { return e / 2 + 4 * (e % 2); }
+
+// a packed word -> its eight inputs as the bf16 integers nibble - 8, k ascending
 __device__ __forceinline__ bf16x8 expand_nibbles(uint32_t w) {
   bf16x8 o;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     // 2^23 + nibble as a float, minus (2^23 + 8): exact
-    const float f = __uint_as_float(0x4B000000u | ((w >> (4 * e)) & 15u)) - 8388616.0f;
+    const float f = __uint_as_float(0x4B000000u | ((w >> (4 * nibble_of(e))) & 15u)) - 8388616.0f;
     o[e] = (bf16)f;
   }
   return o;
 }
 
-// Eight nibbles as the bf16 values 16 + nibble = 24 + q, without a conversion instruction (those run at a quarter
-// of the rate of plain integer instructions here, and sixteen of them per word bound the kernel): in the binade
-// [16, 32) a bf16 is 16 (1 + m / 128), so a nibble placed in the four top bits of the mantissa adds exactly its
-// value.  Two nibbles four apart are placed by one shift and one and-or, so the elements come out in the order
-// 0, 4, 1, 5, 2, 6, 3, 7 (the caller orders the other operand alike).  The constant 24 is taken out again in
-// fp32: sum_k a_k (24 + q_k) - 24 sum_k a_k, with the second sum from an MFMA against ones; the terms are about
-// five times the size of the result, so fp32 loses two or three more bits than without the detour, far below
-// what the rounding of the output, or an fp32 test bar of 1e-5, sees.
+// A packed word as the bf16 values 16 + nibble = 24 + q, k ascending, without a conversion instruction (those run at
+// a quarter of the rate of plain integer instructions here, and sixteen of them per word bound the kernel): in the
+// binade [16, 32) a bf16 is 16 (1 + m / 128), so a nibble placed in the four top bits of the mantissa adds exactly
+// its value.  The storage format puts two neighbours 16 bits apart, so one shift and one and-or place a pair.  The
+// constant 24 is taken out again in fp32: sum_k a_k (24 + q_k) - 24 sum_k a_k, with the second sum from an MFMA
+// against ones; the terms are about five times the size of the result, so fp32 loses two or three more bits than
+// without the detour, far below what the rounding of the output, or an fp32 test bar of 1e-5, sees.
 __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t bits) {      // (x & mask) | bits, one instruction
   uint32_t d;
   asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(bits));
@@ -59,16 +60,6 @@ __device__ __forceinline__ bf16x8 expand_nibbles_plus24(uint32_t w) {
   d[1] = and_or(w >> 1, mask, bits);
   d[2] = and_or(w >> 5, mask, bits);
   d[3] = and_or(w >> 9, mask, bits);
-  return __builtin_bit_cast(bf16x8, d);
-}
-// elements 0..7 -> 0, 4, 1, 5, 2, 6, 3, 7
-__device__ __forceinline__ bf16x8 interleave_halves(bf16x8 a) {
-  const u32x4 r = __builtin_bit_cast(u32x4, a);
-  u32x4 d;
-  d[0] = __builtin_amdgcn_perm(r[2], r[0], 0x05040100u);
-  d[1] = __builtin_amdgcn_perm(r[2], r[0], 0x07060302u);
-  d[2] = __builtin_amdgcn_perm(r[3], r[1], 0x05040100u);
-  d[3] = __builtin_amdgcn_perm(r[3], r[1], 0x07060302u);
   return __builtin_bit_cast(bf16x8, d);
 }
 
@@ -95,7 +86,7 @@ __global__ __launch_bounds__(256) void w4_quantize_kernel(const bf16 *__restrict
   for (int e = 0; e < 8; ++e) {
     float q = sf == 0.f ? 0.f : rintf((float)w[e] / sf);
     q = fminf(fmaxf(q, -(float)(QMAX + 1)), (float)QMAX);
-    word |= (uint32_t)((int)q + 8) << (4 * e);
+    word |= (uint32_t)((int)q + 8) << (4 * nibble_of(e));
   }
   packed[(size_t)n * (K / 8) + g * 16 + l16] = word;
   if (l16 == 0) scales[gid] = scale;
@@ -103,131 +94,10 @@ __global__ __launch_bounds__(256) void w4_quantize_kernel(const bf16 *__restrict
 
 constexpr int EPI_PARTIAL_F32 = ARB_EPI_STORE_F32;   // in a split-K launch split s stores to C + s*M*N
 
+// Epilogue of a 128x128 tile held as 4 waves x (2 x 2) MFMA results (wave (wm, wn) owns rows 64 wm.., columns 64 wn..).
 template <int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict__ A, const uint32_t *__restrict__ Bq,
-                                                      const bf16 *__restrict__ Bscale, void *__restrict__ Cv, int M,
-                                                      int N, int K, int tiles_m, int tiles_n) {
-  __shared__ __attribute__((aligned(16))) bf16 As0[LDS_TILE], As1[LDS_TILE], Bs0[LDS_TILE], Bs1[LDS_TILE];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  int tile_m, tile_n;
-  constexpr int TILE_GROUP = 4;
-  tile_of<TILE_GROUP>(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
-  const int m0 = tile_m * BM;
-  const int frag_row = lane & 31, frag_half = lane >> 5;
-
-  // weight row of tile-local B row r.  SwiGLU: wave column r/64, MFMA tile (r%64)/32 (0 = gate, 1 = up),
-  // feature offset r%32; N = F there and the up rows follow the F gate rows.
-  auto weight_row = [&](int r) {
-    if (EPI == ARB_EPI_SWIGLU_BF16) {
-      const int f = tile_n * 64 + (r >> 6) * 32 + (r & 31);
-      return ((r >> 5) & 1) ? N + f : f;
-    }
-    return tile_n * BN + r;
-  };
-
-  // A: four 16-byte chunks per thread and step, by direct-to-LDS loads (swizzle on the global side)
-  const bf16 *a_src[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = tid + 256 * i, row = c >> 3, chunk = (c & 7) ^ ((row >> 1) & 7);
-    int am = m0 + row;
-    am = am < M ? am : M - 1;                       // tail rows re-read the last row; never stored
-    a_src[i] = A + (size_t)am * K + chunk * 8;
-  }
-  // B: 32 nibbles (16 bytes) of tile row tid/2 per thread and step
-  const int b_row = tid >> 1, b_half = tid & 1;
-  const uint32_t *bq_src = Bq + (size_t)weight_row(b_row) * (K / 8) + b_half * 4;
-  // scales of this lane's two output column tiles
-  const bf16 *sc_src[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) sc_src[j] = Bscale + (size_t)weight_row(wn * 64 + j * 32 + frag_row) * (K / GROUP);
-
-  f32x16 acc[2][2], tmp[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = tmp[i][j][r] = 0.f;
-
-  // K range of this workgroup in whole groups (two steps each)
-  const int ng_all = K / GROUP;
-  const int g_begin = (int)((long long)ng_all * blockIdx.y / gridDim.y);
-  const int ng = (int)((long long)ng_all * (blockIdx.y + 1) / gridDim.y) - g_begin;
-  const int nk = 2 * ng, last = nk - 1;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) a_src[i] += (size_t)g_begin * GROUP;
-  bq_src += (size_t)g_begin * (GROUP / 8);
-
-  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  auto dma_a = [&](int buf, int kt) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * BK), LDS_PTR((buf ? As1 : As0) + (i * 4 + wave_u) * 512), 16, 0, 0);
-  };
-  auto load_b = [&](int kt) { return *(const u32x4 *)(bq_src + (size_t)kt * (BK / 8)); };
-  auto store_b = [&](int buf, u32x4 w) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) *(bf16x8 *)&(buf ? Bs1 : Bs0)[lds_off(b_row, b_half * 4 + c)] = expand_nibbles(w[c]);
-  };
-  auto compute = [&](int buf) {
-    bf16x8 fa[2][2], fb[2][2];
-    auto frags = [&](int slot, int kk) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[slot][i] = *(const bf16x8 *)&(buf ? As1 : As0)[lds_off(wm * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
-        fb[slot][i] = *(const bf16x8 *)&(buf ? Bs1 : Bs0)[lds_off(wn * 64 + i * 32 + frag_row, kk * 2 + frag_half)];
-      }
-    };
-    frags(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) frags((kk + 1) & 1, kk + 1);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          tmp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], tmp[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-
-  // Step kt is multiplied out of stage kt%2 while the A tile of step kt+1 streams into the other stage
-  // and the packed weights of step kt+2 are on their way to registers; the weights of step kt+1 are
-  // expanded into the other stage after the MFMAs of step kt.  Steps come in pairs (one group).
-  dma_a(0, 0);
-  u32x4 bw = load_b(0);
-  store_b(0, bw);
-  bw = load_b(min(1, last));
-  __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
-    const int g = g_begin + (kt >> 1);
-    const float sc0 = (float)sc_src[0][g], sc1 = (float)sc_src[1][g];
-    dma_a(1, kt + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(0);
-    store_b(1, bw);
-    bw = load_b(min(kt + 2, last));
-    __syncthreads();
-    dma_a(0, min(kt + 2, last));
-    __builtin_amdgcn_sched_barrier(0);
-    compute(1);
-    store_b(0, bw);
-    bw = load_b(min(kt + 3, last));
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        acc[i][0][r] = fmaf(tmp[i][0][r], sc0, acc[i][0][r]);
-        acc[i][1][r] = fmaf(tmp[i][1][r], sc1, acc[i][1][r]);
-        tmp[i][0][r] = 0.f;
-        tmp[i][1][r] = 0.f;
-      }
-    __syncthreads();
-  }
-
+__device__ __forceinline__ void w4_tile_epilogue(const f32x16 (&acc)[2][2], void *__restrict__ Cv, int M, int N, int m0,
+                                                 int tile_n, int wm, int wn, int frag_row, int frag_half) {
   // D layout of the 32x32 MFMA: lane holds column lane%32 and rows 8*(r/4) + 4*(lane/32) + r%4.
   if (EPI == ARB_EPI_SWIGLU_BF16) {
     bf16 *C = (bf16 *)Cv;
@@ -264,6 +134,213 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict_
         }
       }
   }
+}
+
+// The tile kernel.  Every wait is counted by hand: left to the compiler, a turn of this loop held three round trips to
+// memory (it waits for all loads in flight before an LDS read that it cannot tell apart from a direct-to-LDS load in
+// flight, and a workgroup fence does so in front of each barrier), and a launch of one tile row (up to 128 tokens, one
+// workgroup per CU) has nothing else to run meanwhile: 75 us on the 8B gate/up shape whatever the row count.  Here the
+// packed weights go to registers six steps ahead and the scales two groups ahead, by inline assembly (the compiler
+// keeps no account of them); the activation tile streams two steps ahead into a ring of three LDS stages; the
+// fragments are read by inline assembly one MFMA step ahead (the compiler sees neither an LDS read that could meet a
+// load in flight nor a load it would have to wait for), and the one wait of a step, in front of its barrier, lets the
+// eight requests made since the tile of the next step stay in flight: loads complete in order, so everything older
+// has landed.  A register that a load in flight will write is named by the wait that covers it (and by a last wait
+// behind the loop): the compiler then neither reads it earlier nor gives it to another value.
+// What bounds it now is the expansion (exact: two integer instructions, a subtraction and half a conversion per
+// weight; without it the 8B gate/up shape at 128 rows takes 41 instead of 59 us, without the MFMAs 56).  The
+// conversion-free expansion of the few-token kernel was tried here too (with the row sums from a third MFMA per
+// row block and, in a second version, two accumulator sets so that the fold of a group runs between the MFMAs of
+// the next): its longer fold (two fused multiply-adds per element and the reads of accumulator registers) costs what
+// the expansion saves, 63-67 us.
+template <int AOFF, int BOFF>
+__device__ __forceinline__ void w4_request_frags(unsigned a_addr, unsigned b_addr, bf16x8 &fa0, bf16x8 &fa1, bf16x8 &fb0,
+                                                 bf16x8 &fb1) {
+  asm volatile("ds_read_b128 %0, %4 offset:%6\n\tds_read_b128 %1, %4 offset:%7\n\t"
+               "ds_read_b128 %2, %5 offset:%8\n\tds_read_b128 %3, %5 offset:%9"
+               : "=&v"(fa0), "=&v"(fa1), "=&v"(fb0), "=&v"(fb1)
+               : "v"(a_addr), "v"(b_addr), "n"(AOFF), "n"(AOFF + 32 * BK * 2), "n"(BOFF), "n"(BOFF + 32 * BK * 2)
+               : "memory");
+}
+// the requested fragments have landed (and every LDS write of this wave is done); naming them keeps their readers behind
+__device__ __forceinline__ void w4_await_frags(bf16x8 &fa0, bf16x8 &fa1, bf16x8 &fb0, bf16x8 &fb1) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa0), "+v"(fa1), "+v"(fb0), "+v"(fb1) : : "memory");
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_w4_kernel(const bf16 *__restrict__ A, const uint32_t *__restrict__ Bq,
+                                                      const bf16 *__restrict__ Bscale, void *__restrict__ Cv, int M,
+                                                      int N, int K, int tiles_m, int tiles_n) {
+  constexpr int NA = 3, AHEAD_W = 6;                    // activation stages; steps the packed weights are ahead
+  // Two objects: the activation ring only ever sees direct-to-LDS loads and the assembly's reads, so the stores of
+  // expanded weights into the other one are not ordered behind loads in flight.
+  __shared__ __attribute__((aligned(16))) bf16 Ring[NA * LDS_TILE], Bs[2 * LDS_TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  constexpr int TILE_GROUP = 4;
+  tile_of<TILE_GROUP>(xcd_remap(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM;
+  const int frag_row = lane & 31, frag_half = lane >> 5;
+
+  // weight row of tile-local B row r.  SwiGLU: wave column r/64, MFMA tile (r%64)/32 (0 = gate, 1 = up),
+  // feature offset r%32; N = F there and the up rows follow the F gate rows.
+  auto weight_row = [&](int r) {
+    if (EPI == ARB_EPI_SWIGLU_BF16) {
+      const int f = tile_n * 64 + (r >> 6) * 32 + (r & 31);
+      return ((r >> 5) & 1) ? N + f : f;
+    }
+    return tile_n * BN + r;
+  };
+
+  const int ng_all = K / GROUP;
+  const int g_begin = (int)((long long)ng_all * blockIdx.y / gridDim.y);
+  const int ng = (int)((long long)ng_all * (blockIdx.y + 1) / gridDim.y) - g_begin;
+  const int nk = 2 * ng, last = nk - 1;
+
+  const bf16 *a_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tid + 256 * i, row = c >> 3, chunk = (c & 7) ^ ((row >> 1) & 7);
+    int am = m0 + row;
+    am = am < M ? am : M - 1;                            // tail rows re-read the last row; never stored
+    a_src[i] = A + (size_t)am * K + (size_t)g_begin * GROUP + chunk * 8;
+  }
+  const int b_row = tid >> 1, b_half = tid & 1;
+  const uint32_t *bq_src = Bq + (size_t)weight_row(b_row) * (K / 8) + (size_t)g_begin * (GROUP / 8) + b_half * 4;
+  const bf16 *sc_src[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) sc_src[j] = Bscale + (size_t)weight_row(wn * 64 + j * 32 + frag_row) * (K / GROUP) + g_begin;
+
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma_a = [&](int stage, int kt) {                  // four wave-wide direct-to-LDS loads
+    kt = kt < last ? kt : last;                          // past the range: a valid step, never read
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(a_src[i] + (size_t)kt * BK), LDS_PTR(Ring + stage * LDS_TILE + (i * 4 + wave_u) * 512), 16, 0, 0);
+  };
+  u32x4 wq[AHEAD_W];                                     // packed weights of steps kt+1 .. kt+6, slot = step % 6
+  unsigned sc[3][2];                                     // scales (bf16 bits) of three groups, slot = group % 3
+  auto load_w = [&](int slot, int kt) {
+    kt = kt < last ? kt : last;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(wq[slot]) : "v"(bq_src + (size_t)kt * (BK / 8)) : "memory");
+  };
+  auto load_sc = [&](int slot, int g) {
+    g = g < ng ? g : ng - 1;
+    asm volatile("global_load_ushort %0, %1, off" : "=&v"(sc[slot][0]) : "v"(sc_src[0] + g) : "memory");
+    asm volatile("global_load_ushort %0, %1, off" : "=&v"(sc[slot][1]) : "v"(sc_src[1] + g) : "memory");
+  };
+  auto store_b = [&](int buf, const u32x4 &w) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) *(bf16x8 *)&Bs[buf * LDS_TILE + lds_off(b_row, b_half * 4 + c)] = expand_nibbles(w[c]);
+  };
+
+  // byte addresses of this lane's fragments of MFMA step kk in stage 0: the row block's first row; the second row
+  // block, the stage and the operand's array are constant displacements
+  unsigned a_addr[4], b_addr[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    a_addr[kk] = (unsigned)(uintptr_t)LDS_PTR(Ring) + 2u * lds_off(wm * 64 + frag_row, kk * 2 + frag_half);
+    b_addr[kk] = (unsigned)(uintptr_t)LDS_PTR(Bs) + 2u * lds_off(wn * 64 + frag_row, kk * 2 + frag_half);
+  }
+
+  f32x16 acc[2][2], tmp[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = tmp[i][j][r] = 0.f;
+
+  // Request order of the prologue = that of the loop: (tile, weights[, scales]) per step, the scales on even steps.
+#pragma unroll
+  for (int d = 0; d < AHEAD_W - 1; ++d) load_w(d, d);
+  load_sc(0, 0);
+  load_sc(1, 1);
+  asm volatile("" ::: "memory");
+  dma_a(0, 0);
+  asm volatile("" ::: "memory");
+  dma_a(1, 1);
+  asm volatile("" ::: "memory");
+  load_w(AHEAD_W - 1, AHEAD_W - 1);
+  // all but the second tile and the last weights have landed; a wait names the registers whose loads it covers and
+  // that are read before the next wait does so, or the compiler could move their readers above it
+  asm volatile("s_waitcnt vmcnt(5)" : "+v"(wq[0]), "+v"(wq[1]), "+v"(sc[0][0]), "+v"(sc[0][1]) : : "memory");
+  store_b(0, wq[0]);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+
+  bf16x8 fa[2][2], fb[2][2];
+  // One step (64 k): u = its position in a turn of six (three groups), so that stage (u % 3), weight stage (u % 2),
+  // register set (u % 6) and scale set are fixed per position.
+  auto step = [&](auto u_, int kt) {
+    constexpr int U = decltype(u_)::value;
+    constexpr int SA = (U % NA) * LDS_TILE * 2, SB = (U % 2) * LDS_TILE * 2;
+    dma_a((U + 2) % NA, kt + 2);                         // into the stage step kt-1 was read from
+    asm volatile("" ::: "memory");
+    load_w(U % AHEAD_W, kt + AHEAD_W);                   // that set went into LDS during step kt-1
+    if (U % 2 == 0) load_sc((U / 2 + 2) % 3, (kt >> 1) + 2);
+    asm volatile("" ::: "memory");
+    w4_request_frags<SA, SB>(a_addr[0], b_addr[0], fa[0][0], fa[0][1], fb[0][0], fb[0][1]);
+    const u32x4 &next_w = wq[(U + 1) % AHEAD_W];
+    bf16 *next_b = Bs + ((U + 1) % 2) * LDS_TILE;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      w4_await_frags(fa[kk & 1][0], fa[kk & 1][1], fb[kk & 1][0], fb[kk & 1][1]);
+      if (kk == 0) w4_request_frags<SA, SB>(a_addr[1], b_addr[1], fa[1][0], fa[1][1], fb[1][0], fb[1][1]);
+      if (kk == 1) w4_request_frags<SA, SB>(a_addr[2], b_addr[2], fa[0][0], fa[0][1], fb[0][0], fb[0][1]);
+      if (kk == 2) w4_request_frags<SA, SB>(a_addr[3], b_addr[3], fa[1][0], fa[1][1], fb[1][0], fb[1][1]);
+      // the MFMAs stay behind the request (left alone, the scheduler moves them up and the wave then waits out the
+      // LDS latency of every request with nothing to do)
+      __builtin_amdgcn_sched_barrier(0);
+      // a quarter of the next step's weights per MFMA step: expanded and stored while the matrix pipe runs
+      *(bf16x8 *)&next_b[lds_off(b_row, b_half * 4 + kk)] = expand_nibbles(next_w[kk]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          tmp[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], tmp[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (U % 2 == 1) {                                    // end of a group
+      const float s0 = __uint_as_float(sc[U / 2][0] << 16), s1 = __uint_as_float(sc[U / 2][1] << 16);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          acc[i][0][r] = fmaf(tmp[i][0][r], s0, acc[i][0][r]);
+          acc[i][1][r] = fmaf(tmp[i][1][r], s1, acc[i][1][r]);
+          tmp[i][0][r] = 0.f;
+          tmp[i][1][r] = 0.f;
+        }
+    }
+    // The tile of step kt+1 was requested at the top of step kt-1; since then: that step's weights, this step's
+    // tile and weights, and the scales of whichever of the two steps is even: 1 + 4 + 1 + 2 = 8 requests.
+    // Everything older has landed, among it the weights the next step expands and the scales the next step folds in.
+    if (U % 2 == 0)
+      asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" : "+v"(wq[(U + 2) % AHEAD_W]), "+v"(sc[U / 2][0]), "+v"(sc[U / 2][1]) : : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" : "+v"(wq[(U + 2) % AHEAD_W]) : : "memory");
+    __builtin_amdgcn_s_barrier();
+  };
+  for (int kt = 0; kt < nk; kt += 6) {
+    step(std::integral_constant<int, 0>{}, kt);
+    step(std::integral_constant<int, 1>{}, kt + 1);
+    if (kt + 2 >= nk) break;
+    step(std::integral_constant<int, 2>{}, kt + 2);
+    step(std::integral_constant<int, 3>{}, kt + 3);
+    if (kt + 4 >= nk) break;
+    step(std::integral_constant<int, 4>{}, kt + 4);
+    step(std::integral_constant<int, 5>{}, kt + 5);
+  }
+  // The clamped requests past the end: their registers stay named until they have landed (a register the compiler
+  // takes for dead it hands to something else, and a load that lands in it afterwards overwrites that).
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(wq[0]), "+v"(wq[1]), "+v"(wq[2]), "+v"(wq[3]), "+v"(wq[4]), "+v"(wq[5]), "+v"(sc[0][0]), "+v"(sc[0][1]),
+                 "+v"(sc[1][0]), "+v"(sc[1][1]), "+v"(sc[2][0]), "+v"(sc[2][1])
+               : : "memory");
+  w4_tile_epilogue<EPI>(acc, Cv, M, N, m0, tile_n, wm, wn, frag_row, frag_half);
 }
 
 
@@ -395,8 +472,12 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
         // followed the tile, NW > NS = 2), or at most (NS - 2) (MR / 4 + 6) = 20 (NW == NS = 4).  The wave reads
         // only its own tile, so no barrier is needed.
         static_assert((NS == 2 && NW > NS) || (NS == 4 && NW == NS && (NS - 2) * (MR / 4 + 6) == 20), "the counted waits below");
-        if (NS == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+        // (the wait names the registers of the set it covers, so that the compiler keeps their readers behind it)
+        Fetched &got = f[u];
+#define ARB_W4_COVERED "+v"(got.w[0][0]), "+v"(got.w[0][1]), "+v"(got.w[1][0]), "+v"(got.w[1][1]), "+v"(got.s[0]), "+v"(got.s[1])
+        if (NS == 2) asm volatile("s_waitcnt vmcnt(6)" : ARB_W4_COVERED : : "memory");
+        else asm volatile("s_waitcnt vmcnt(20)" : ARB_W4_COVERED : : "memory");
+#undef ARB_W4_COVERED
         dma_a(gg + 4 * (NS - 1), (u + NS - 1) % NS);
         asm volatile("" ::: "memory");
         load_w(gg + 4 * (NW - 1), f[(u + NW - 1) % NW]);
@@ -407,7 +488,7 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
         read_frags(u % NS, frags);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const bf16x8 fa = interleave_halves(frags[i]);
+          const bf16x8 fa = frags[i];
           tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_plus24(cur.w[0][i >> 2][i & 3]), tmp[0], 0, 0, 0);
           tmp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, expand_nibbles_plus24(cur.w[1][i >> 2][i & 3]), tmp[1], 0, 0, 0);
           asum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, ones, asum, 0, 0, 0);
@@ -422,6 +503,13 @@ __global__ __launch_bounds__(256, 2) void gemm_w4_skinny_kernel(const bf16 *__re
         }
       }
     }
+    // The clamped requests past the range: their registers stay named until they have landed (a register the compiler
+    // takes for dead it hands to something else, and a load that lands in it afterwards overwrites that).
+#pragma unroll
+    for (int d = 0; d < NW; ++d)
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(f[d].w[0][0]), "+v"(f[d].w[0][1]), "+v"(f[d].w[1][0]), "+v"(f[d].w[1][1]), "+v"(f[d].s[0]), "+v"(f[d].s[1])
+                   : : "memory");
   }
 
   __syncthreads();                                       // every wave is done with its stage reads (and loads)

@@ -732,7 +732,11 @@ def test_gemm_takes_3bit_weights_in_the_nibble_format(A, M):
                                        (1024, 4480, 1536, "swiglu"),
                                        # up to 32 rows the weight-streaming kernel runs (33: the tile kernel again)
                                        (32, 2048, 4096, "store"), (7, 8960, 1536, "swiglu"), (32, 256, 1536, "residual"),
-                                       (5, 256, 384, "f32"), (33, 256, 1536, "residual"), (17, 14336, 4096, "swiglu")])
+                                       (5, 256, 384, "f32"), (33, 256, 1536, "residual"), (17, 14336, 4096, "swiglu"),
+                                       # the tile kernel walks K in turns of six steps (three groups of 128): every
+                                       # way of leaving a turn, and one tile row of the 8B width
+                                       (64, 128, 128, "f32"), (100, 128, 256, "f32"), (128, 256, 384, "store"),
+                                       (40, 128, 896, "f32"), (129, 256, 1024, "residual"), (96, 3584, 4096, "swiglu")])
 def test_w4_gemm(A, M, N, K, epi):
     rows = 2 * N if epi == "swiglu" else N
     a, w = rand_bf16((M, K), 1.0, 52), rand_bf16((rows, K), 0.05, 53)

@@ -648,11 +648,14 @@ def test_w4_quantization_definition():
     # integers times the scale are fixed points
     again, sb2 = O.w4_quantize(O.float_to_bf16(7 * np.repeat(s, 128, 1) * np.sign(r.normal(size=(6, 384)))))
     assert np.array_equal(sb2, sb) and np.all(np.abs(again[np.repeat(s, 128, 1) > 0]) == 7)
-    # packing: nibble j of word i is q[8i + j] + 8
+    # packing: word i holds q[8i .. 8i+7] + 8, the even ones in nibbles 0..3, the odd ones in nibbles 4..7
     p = O.w4_pack(q)
     assert p.dtype == np.uint32 and p.shape == (6, 48)
-    for (n, k) in ((0, 0), (3, 77), (5, 383)):
-        assert (int(p[n, k // 8]) >> (4 * (k % 8))) & 15 == int(q[n, k]) + 8
+    for (n, k) in ((0, 0), (0, 1), (3, 77), (3, 78), (5, 382), (5, 383)):
+        nibble = (k % 8) // 2 + 4 * (k % 2)
+        assert (int(p[n, k // 8]) >> (4 * nibble)) & 15 == int(q[n, k]) + 8
+    one = np.zeros((1, 128), np.int8); one[0, :8] = [-8, -7, -6, -5, -4, -3, -2, -1]
+    assert int(O.w4_pack(one)[0, 0]) == 0x75316420
 
 
 def test_w3_quantization_is_the_same_rule_with_levels_minus4_to_3():
@@ -675,7 +678,7 @@ def test_w3_quantization_is_the_same_rule_with_levels_minus4_to_3():
     assert 1.8 < e3 / e4 < 2.9
     # the nibble format holds them unchanged
     p = O.w4_pack(q)
-    assert (int(p[4, 31]) >> 28) & 15 == int(q[4, 255]) + 8
+    assert (int(p[4, 31]) >> 28) & 15 == int(q[4, 255]) + 8 and (int(p[4, 31]) >> 12) & 15 == int(q[4, 254]) + 8
     with pytest.raises(ValueError):
         O.w4_quantize(w, bits=5)
 
